@@ -1,0 +1,87 @@
+/*
+ * CPU oracle for DistrAttention (arXiv 2507.17245) -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, fp64 implementation of
+ *   - exact attention, S = QK^T -> softmax -> PV                       (Sec. 2.1)
+ *   - the DistrAttention approximation: LSH over the channel columns of
+ *     each Q block, sort, fixed-size groups, sample one Q column per
+ *     group, sum the group's K columns, S^ = Q_r K_f^T                 (Sec. 3.1 Eq. 2,
+ *     Sec. 3.2, Sec. 3.3)
+ * It shares no code with the GPU library and is only called from the
+ * tests, the smoke check and the benchmark's cpu_baseline leg.
+ *
+ * All pointers are host pointers. q and o are [B][H][N][d], k and v are
+ * [B][Hkv][N][d], contiguous, d fastest. Inputs are float (bf16 workloads
+ * pass bf16-representable floats), every dot product, sum and softmax is
+ * taken in double, outputs are double. The one exception is the LSH
+ * projection, whose sign decides an integer: it is taken in float with one
+ * fused multiply-add per row in ascending row order, the precision and
+ * order the GPU kernel uses, so the group tables can be compared bit by bit.
+ *
+ * Every function returns 0 on success and a negative value on bad arguments.
+ */
+#ifndef DISTR_ATTN_ORACLE_H
+#define DISTR_ATTN_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+  int B, H, Hkv, N, d;
+  int Br;         /* rows of a Q block (the paper's l): one grouping per block (Sec. 3.3) */
+  int n_groups;   /* k = d / G*                                            (Sec. 3.2)  */
+  int causal;     /* key n visible to query i iff n <= i */
+  int n_planes;   /* the paper's N' (16 in Sec. 3.2), 1..32 */
+  int gray_mode;  /* 0: hash = rank of the sign word read as a Gray codeword; 1: hash = sign word Gray-encoded */
+  uint64_t lsh_seed;
+  double scale;   /* multiplies S before softmax */
+} oracle_params;
+
+/* Projection matrix R[n_planes][Br] from the seed (counter-based, exactly representable floats). */
+int oracle_hyperplanes(uint64_t seed, int n_planes, int Br, float *R);
+
+/* Gray map of one sign word. */
+uint32_t oracle_gray_hash(uint32_t code, int n_planes, int gray_mode);
+
+/* Ascending stable sort of d hashes (ties keep ascending channel index): perm[s] = channel at
+ * sorted position s (Fig. 5). */
+int oracle_sort_channels(const uint32_t *hash, int d, uint8_t *perm);
+
+/* LSH grouping of every Q block with an explicit projection matrix R[n_planes][Br].
+ * hash_out, perm_out: [B][H][Tq][d], Tq = ceil(N/Br); either may be NULL.
+ * proj_out (may be NULL): [B][H][Tq][d][n_planes] float projections. */
+int oracle_lsh_group(const float *q, const oracle_params *p, const float *R,
+                     uint32_t *hash_out, uint8_t *perm_out, float *proj_out);
+
+/* Exact attention, all rows. */
+int oracle_exact_fwd(const float *q, const float *k, const float *v, double *o,
+                     const oracle_params *p);
+
+/* DistrAttention, all rows. R may be NULL (then it comes from p->lsh_seed).
+ * perm (may be NULL) overrides the LSH grouping: [B][H][Tq][d]. */
+int oracle_distr_fwd(const float *q, const float *k, const float *v, double *o,
+                     const oracle_params *p, const float *R, const uint8_t *perm);
+
+/* The same two, restricted to a list of Q blocks: tiles[3*i+0..2] = (b, h, t).
+ * o_tiles is [n_tiles][Br][d]; rows past N in a ragged block are left untouched. */
+int oracle_exact_fwd_tiles(const float *q, const float *k, const float *v, double *o_tiles,
+                           const oracle_params *p, const int *tiles, int n_tiles);
+int oracle_distr_fwd_tiles(const float *q, const float *k, const float *v, double *o_tiles,
+                           const oracle_params *p, const float *R, const uint8_t *perm,
+                           const int *tiles, int n_tiles);
+
+/* Unnormalised score blocks for one (b, h): s_hat and s are [N][N] doubles
+ * (scale applied, no mask). Either may be NULL. */
+int oracle_scores(const float *q, const float *k, double *s_hat, double *s,
+                  const oracle_params *p, const float *R, const uint8_t *perm, int b, int h);
+
+/* Threads the parallel loops will use. */
+int oracle_num_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
