@@ -1,0 +1,113 @@
+/*
+ * distr_attn -- DistrAttention block-wise attention forward pass for AMD MI355X (gfx950).
+ *
+ * C ABI of libdistr_attn.so. Method: "DistrAttention: An Efficient and Flexible
+ * Self-Attention Mechanism on Modern GPUs" (arXiv 2507.17245), cited below by section.
+ *
+ * Conventions for every entry point
+ *   - q, k, v, o and every pointer named *_out / workspace are DEVICE pointers owned by the
+ *     caller; `const da_params*` and `float* host_out` are HOST pointers.
+ *   - Layout: q and o are [B][H][N][d]; k and v are [B][Hkv][N][d]; contiguous, d fastest.
+ *     Query head h reads key/value head h / (H / Hkv). Element type is bf16 or float (da_dtype).
+ *   - q, k, v are never written. o must not alias an input. Base pointers must be 16-byte aligned.
+ *   - Calls only enqueue work on the stream (asynchronous); they never synchronise the device.
+ *   - Return value: DA_OK or a negative da_status. All argument checks run on the host before
+ *     anything is launched; on error nothing has been enqueued. distr_attn_last_error() gives a
+ *     message for the last failure on the calling thread.
+ *   - Notation: Tq = ceil(N / Br) query blocks; G* = d / n_groups channels per group.
+ */
+#ifndef DISTR_ATTN_H
+#define DISTR_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DA_OK = 0,
+  DA_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, H % Hkv != 0, d % n_groups != 0, misaligned */
+  DA_ERR_UNSUPPORTED = -2, /* valid for the method, outside what the kernels are built for */
+  DA_ERR_WORKSPACE = -3,   /* caller workspace too small, or the library could not allocate its own */
+  DA_ERR_HIP = -4          /* a HIP runtime call failed */
+} da_status;
+
+typedef enum { DA_BF16 = 0, DA_F32 = 1 } da_dtype;
+
+/*
+ * Full parameter block (host memory).
+ *
+ * Supported by the kernels: d in {64, 128}; Br in {64, 128}; Bc = 64; n_groups a multiple
+ * of 16 for bf16 (the MFMA contraction step) and any divisor of d for float; 1 <= n_planes <= 32;
+ * N >= 1 arbitrary (ragged last blocks are masked).
+ */
+typedef struct {
+  int B, H, Hkv, N, d;
+  int Br;               /* rows of a query block, the paper's l; one LSH grouping per block (Sec. 3.3) */
+  int Bc;               /* rows of a key/value block, the paper's m (Sec. 2.2.2)                     */
+  int n_groups;         /* k = d / G*: contraction length of S^ = Q_r K_f^T (Sec. 3.1 Eq. 2, Sec. 3.2) */
+  int causal;           /* 0 / 1: key n is visible to query i iff n <= i                            */
+  uint64_t lsh_seed;    /* seed of the random projection matrix (Sec. 3.2)                          */
+  int dtype;            /* da_dtype of q, k, v, o                                                   */
+  int n_planes;         /* number of projections N' (Sec. 3.2 uses 16); 0 means 16                  */
+  float softmax_scale;  /* multiplies S before softmax; 0 means 1/sqrt(d)                           */
+  int gray_mode;        /* Gray map of the sign word (Sec. 3.2): 0 = position of the word in the Gray
+                           sequence, 1 = Gray code of the word                                     */
+  void *stream;         /* hipStream_t; NULL = the stream set by distr_attn_set_stream (default: null stream) */
+  void *workspace;      /* device scratch of >= distr_attn_workspace_bytes(); NULL = library-owned,
+                           grown on demand (hipMalloc on first use / growth)                        */
+  size_t workspace_bytes;
+  uint8_t *perm_out;    /* optional device [B][H][Tq][d]: channel at sorted position s of each block */
+  uint32_t *hash_out;   /* optional device [B][H][Tq][d]: hash of each channel of each block          */
+} da_params;
+
+/*
+ * DistrAttention forward (Sec. 3.1-3.3): per query block, hash the d channel columns with
+ * random-projection LSH, sort the hashes, cut the sorted order into groups of G*, take the first
+ * channel of each group from Q and the sum of the group's channels from K, S^ = Q_r K_f^T, then
+ * online softmax and P V over the full V. bf16, 16 projections, scale 1/sqrt(d), current stream.
+ */
+int distr_attn_fwd(const void *q, const void *k, const void *v, void *o, int B, int H, int Hkv,
+                   int N, int d, int Br, int Bc, int n_groups, uint64_t lsh_seed, int causal);
+
+/* Exact attention forward, O = softmax(scale * Q K^T) V (Sec. 2.1), tiled the same way (Sec. 2.2.2). */
+int distr_attn_exact_fwd(const void *q, const void *k, const void *v, void *o, int B, int H,
+                         int Hkv, int N, int d, int Br, int Bc, int causal);
+
+/* The same two operations with every option of da_params. */
+int distr_attn_fwd_ex(const void *q, const void *k, const void *v, void *o, const da_params *p);
+int distr_attn_exact_fwd_ex(const void *q, const void *k, const void *v, void *o, const da_params *p);
+
+/*
+ * LSH hash-and-group stage alone (Sec. 3.2 "similar columns identification", Fig. 5): writes
+ * p->perm_out and/or p->hash_out (at least one must be given). Projections are accumulated in
+ * float with one fused multiply-add per row, rows ascending; bit of plane 0 is the most
+ * significant; channels are sorted by (hash, channel index) ascending.
+ */
+int distr_attn_lsh_group(const void *q, const da_params *p);
+
+/* Bytes of device scratch distr_attn_fwd_ex needs for p (0 on invalid p). */
+size_t distr_attn_workspace_bytes(const da_params *p);
+
+/*
+ * The projection matrix the GPU path uses for (seed, n_planes, Br): host_out[n_planes][Br] floats
+ * (host memory). Entry (p, r) depends on (seed, p, r) only. Sec. 3.2 asks for a fixed random
+ * matrix; the generator is a counter-based integer mixer whose outputs are exact dyadic floats.
+ */
+int distr_attn_hyperplanes(uint64_t seed, int n_planes, int Br, float *host_out);
+
+/* Stream used when da_params.stream is NULL and by the short-form entry points (process-wide). */
+int distr_attn_set_stream(void *hip_stream);
+
+/* Frees library-owned device memory (workspace, cached projection matrices). */
+int distr_attn_release(void);
+
+const char *distr_attn_last_error(void);
+const char *distr_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

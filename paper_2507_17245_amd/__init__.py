@@ -1,0 +1,180 @@
+"""Python binding of libdistr_attn.so (DistrAttention forward for MI355X / gfx950).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.
+Tensors are torch tensors on the GPU (torch provides device memory and streams, nothing
+else); names mirror the C entry points declared in include/distr_attn.h. There is no
+fallback: a missing library or a failing call raises.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdistr_attn.so")
+
+DA_OK, DA_ERR_INVALID_ARG, DA_ERR_UNSUPPORTED, DA_ERR_WORKSPACE, DA_ERR_HIP = 0, -1, -2, -3, -4
+DA_BF16, DA_F32 = 0, 1
+
+EXPORTS = (
+    "distr_attn_fwd", "distr_attn_exact_fwd", "distr_attn_fwd_ex", "distr_attn_exact_fwd_ex",
+    "distr_attn_lsh_group", "distr_attn_workspace_bytes", "distr_attn_hyperplanes",
+    "distr_attn_set_stream", "distr_attn_release", "distr_attn_last_error", "distr_attn_version",
+)
+
+
+class DaParams(ctypes.Structure):
+    """Mirror of da_params."""
+    _fields_ = [
+        ("B", ctypes.c_int), ("H", ctypes.c_int), ("Hkv", ctypes.c_int), ("N", ctypes.c_int),
+        ("d", ctypes.c_int), ("Br", ctypes.c_int), ("Bc", ctypes.c_int), ("n_groups", ctypes.c_int),
+        ("causal", ctypes.c_int), ("lsh_seed", ctypes.c_uint64), ("dtype", ctypes.c_int),
+        ("n_planes", ctypes.c_int), ("softmax_scale", ctypes.c_float), ("gray_mode", ctypes.c_int),
+        ("stream", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+        ("workspace_bytes", ctypes.c_size_t), ("perm_out", ctypes.c_void_p),
+        ("hash_out", ctypes.c_void_p),
+    ]
+
+
+class DistrAttnError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"distr_attn error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library. Raises if it has not been built (python -m paper_2507_17245_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2507_17245_amd/build.py`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64
+        L.distr_attn_fwd.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, u64, ci]
+        L.distr_attn_exact_fwd.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci]
+        for name in ("distr_attn_fwd_ex", "distr_attn_exact_fwd_ex"):
+            getattr(L, name).argtypes = [vp, vp, vp, vp, ctypes.POINTER(DaParams)]
+        L.distr_attn_lsh_group.argtypes = [vp, ctypes.POINTER(DaParams)]
+        L.distr_attn_workspace_bytes.argtypes = [ctypes.POINTER(DaParams)]
+        L.distr_attn_workspace_bytes.restype = ctypes.c_size_t
+        L.distr_attn_hyperplanes.argtypes = [u64, ci, ci, ctypes.POINTER(ctypes.c_float)]
+        L.distr_attn_set_stream.argtypes = [vp]
+        L.distr_attn_last_error.restype = ctypes.c_char_p
+        L.distr_attn_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != DA_OK:
+        raise DistrAttnError(rc, lib().distr_attn_last_error().decode())
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _current_stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return DA_BF16
+    if t.dtype == torch.float32:
+        return DA_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _shapes(q, k, v):
+    if q.dim() != 4 or k.dim() != 4 or v.shape != k.shape:
+        raise ValueError("q must be [B,H,N,d]; k, v must be [B,Hkv,N,d]")
+    B, H, N, d = q.shape
+    if k.shape[0] != B or k.shape[2] != N or k.shape[3] != d:
+        raise ValueError("k, v do not match q")
+    for t in (q, k, v):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous and on the GPU")
+    if not (q.dtype == k.dtype == v.dtype):
+        raise TypeError("q, k, v must share a dtype")
+    return B, H, k.shape[1], N, d
+
+
+def make_params(q, k, v, Br, Bc=64, n_groups=None, causal=False, lsh_seed=0, n_planes=0,
+                softmax_scale=0.0, gray_mode=0, workspace=None, perm_out=None, hash_out=None):
+    B, H, Hkv, N, d = _shapes(q, k, v)
+    p = DaParams()
+    p.B, p.H, p.Hkv, p.N, p.d, p.Br, p.Bc = B, H, Hkv, N, d, Br, Bc
+    p.n_groups = d if n_groups is None else n_groups
+    p.causal = int(bool(causal))
+    p.lsh_seed = lsh_seed
+    p.dtype = _dtype_code(q)
+    p.n_planes = n_planes
+    p.softmax_scale = softmax_scale
+    p.gray_mode = gray_mode
+    p.stream = _current_stream().value
+    if workspace is not None:
+        p.workspace = workspace.data_ptr()
+        p.workspace_bytes = workspace.numel() * workspace.element_size()
+    p.perm_out = perm_out.data_ptr() if perm_out is not None else None
+    p.hash_out = hash_out.data_ptr() if hash_out is not None else None
+    return p
+
+
+def distr_attn_fwd(q, k, v, o, Br, Bc, n_groups, lsh_seed=0, causal=False):
+    """Short form: bf16, 16 projections, scale 1/sqrt(d), on torch's current stream."""
+    B, H, Hkv, N, d = _shapes(q, k, v)
+    if _dtype_code(q) != DA_BF16:
+        raise TypeError("the short form takes bf16 tensors; use distr_attn_fwd_ex for float")
+    lib().distr_attn_set_stream(_current_stream())
+    _check(lib().distr_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), B, H, Hkv, N, d, Br, Bc,
+                                n_groups, lsh_seed, int(bool(causal))))
+    return o
+
+
+def distr_attn_exact_fwd(q, k, v, o, Br, Bc, causal=False):
+    B, H, Hkv, N, d = _shapes(q, k, v)
+    if _dtype_code(q) != DA_BF16:
+        raise TypeError("the short form takes bf16 tensors; use distr_attn_exact_fwd_ex for float")
+    lib().distr_attn_set_stream(_current_stream())
+    _check(lib().distr_attn_exact_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), B, H, Hkv, N, d, Br, Bc,
+                                      int(bool(causal))))
+    return o
+
+
+def distr_attn_fwd_ex(q, k, v, o, params):
+    _check(lib().distr_attn_fwd_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(o), ctypes.byref(params)))
+    return o
+
+
+def distr_attn_exact_fwd_ex(q, k, v, o, params):
+    _check(lib().distr_attn_exact_fwd_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(o), ctypes.byref(params)))
+    return o
+
+
+def distr_attn_lsh_group(q, params):
+    _check(lib().distr_attn_lsh_group(_ptr(q), ctypes.byref(params)))
+
+
+def distr_attn_workspace_bytes(params):
+    return int(lib().distr_attn_workspace_bytes(ctypes.byref(params)))
+
+
+def distr_attn_hyperplanes(seed, n_planes, Br):
+    """-> numpy float32 [n_planes, Br] (host): the projection matrix the kernels generate."""
+    import numpy as np
+    out = np.empty((n_planes, Br), dtype=np.float32)
+    _check(lib().distr_attn_hyperplanes(seed, n_planes, Br,
+                                        out.ctypes.data_as(ctypes.POINTER(ctypes.c_float))))
+    return out
+
+
+def distr_attn_release():
+    _check(lib().distr_attn_release())
+
+
+def distr_attn_version():
+    return lib().distr_attn_version().decode()

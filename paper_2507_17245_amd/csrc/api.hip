@@ -1,0 +1,223 @@
+// C ABI of libdistr_attn.so: argument checks, workspace, launches. See include/distr_attn.h.
+#include "../../include/distr_attn.h"
+
+#include <atomic>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <mutex>
+
+#include "da_common.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+std::atomic<void*> g_stream{nullptr};
+
+std::mutex g_ws_mutex;
+void* g_ws_ptr[16] = {nullptr};     // library-owned workspace, one per device
+size_t g_ws_bytes[16] = {0};
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+struct Resolved {
+  da::Problem pb;
+  int dtype;
+  int Tq;
+  hipStream_t stream;
+};
+
+// Checks shared by every entry point. need_groups: the call uses the LSH grouping.
+int resolve(const da_params* p, bool need_groups, Resolved* out) {
+  if (!p) return fail(DA_ERR_INVALID_ARG, "params is null");
+  if (p->B <= 0 || p->H <= 0 || p->Hkv <= 0 || p->N <= 0 || p->d <= 0 || p->Br <= 0 || p->Bc <= 0)
+    return fail(DA_ERR_INVALID_ARG, "B, H, Hkv, N, d, Br, Bc must be positive");
+  if (p->H % p->Hkv != 0) return fail(DA_ERR_INVALID_ARG, "H (%d) is not a multiple of Hkv (%d)", p->H, p->Hkv);
+  if (p->dtype != DA_BF16 && p->dtype != DA_F32) return fail(DA_ERR_INVALID_ARG, "unknown dtype %d", p->dtype);
+  if (p->causal != 0 && p->causal != 1) return fail(DA_ERR_INVALID_ARG, "causal must be 0 or 1");
+  int n_planes = p->n_planes == 0 ? 16 : p->n_planes;
+  if (need_groups) {
+    if (p->n_groups <= 0 || p->d % p->n_groups != 0)
+      return fail(DA_ERR_INVALID_ARG, "n_groups (%d) must divide d (%d): groups have a constant size", p->n_groups, p->d);
+    if (n_planes < 1) return fail(DA_ERR_INVALID_ARG, "n_planes must be positive");
+    if (p->gray_mode != 0 && p->gray_mode != 1) return fail(DA_ERR_INVALID_ARG, "gray_mode must be 0 or 1");
+  }
+  float scale = p->softmax_scale;
+  if (scale == 0.0f) scale = 1.0f / std::sqrt((float)p->d);
+  if (!(scale > 0.0f) || !std::isfinite(scale)) return fail(DA_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
+  if ((long long)p->B * p->H * ((p->N + p->Br - 1) / p->Br) > 0x7fffffffLL)
+    return fail(DA_ERR_UNSUPPORTED, "more than 2^31-1 query blocks");
+  // limits of the kernels
+  if (p->d != 64 && p->d != 128) return fail(DA_ERR_UNSUPPORTED, "d = %d: kernels are built for d in {64, 128}", p->d);
+  if (p->Br != 64 && p->Br != 128) return fail(DA_ERR_UNSUPPORTED, "Br = %d: kernels are built for Br in {64, 128}", p->Br);
+  if (p->Bc != 64) return fail(DA_ERR_UNSUPPORTED, "Bc = %d: kernels are built for Bc = 64", p->Bc);
+  if (need_groups && n_planes > da::kMaxPlanes) return fail(DA_ERR_UNSUPPORTED, "n_planes = %d > %d", n_planes, da::kMaxPlanes);
+  out->pb = da::Problem{p->B, p->H, p->Hkv, p->N, p->d, p->Br, need_groups ? p->n_groups : p->d,
+                        p->causal, n_planes, p->gray_mode, p->lsh_seed, scale};
+  out->dtype = p->dtype;
+  out->Tq = (p->N + p->Br - 1) / p->Br;
+  out->stream = (hipStream_t)(p->stream ? p->stream : g_stream.load());
+  return DA_OK;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+int check_tensors(const void* q, const void* k, const void* v, const void* o) {
+  if (!q || !k || !v || !o) return fail(DA_ERR_INVALID_ARG, "q, k, v, o must be non-null");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
+    return fail(DA_ERR_INVALID_ARG, "q, k, v, o must be 16-byte aligned");
+  if (o == q || o == k || o == v) return fail(DA_ERR_INVALID_ARG, "o must not alias an input");
+  return DA_OK;
+}
+
+size_t perm_bytes(const Resolved& r) {
+  size_t n = (size_t)r.pb.B * r.pb.H * r.Tq * r.pb.d;
+  return (n + 255) & ~(size_t)255;
+}
+
+// Device buffer for the permutation table: caller's perm_out, caller's workspace, or ours.
+int get_perm_buffer(const da_params* p, const Resolved& r, uint8_t** out) {
+  if (p->perm_out) { *out = p->perm_out; return DA_OK; }
+  const size_t need = perm_bytes(r);
+  if (p->workspace) {
+    if (p->workspace_bytes < need)
+      return fail(DA_ERR_WORKSPACE, "workspace of %zu bytes, %zu needed", p->workspace_bytes, need);
+    *out = (uint8_t*)p->workspace;
+    return DA_OK;
+  }
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(DA_ERR_HIP, "hipGetDevice failed");
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  if (g_ws_bytes[dev] < need) {
+    if (g_ws_ptr[dev]) {
+      // the old buffer may still be read by enqueued work
+      if (hipDeviceSynchronize() != hipSuccess) return fail(DA_ERR_HIP, "hipDeviceSynchronize failed");
+      (void)hipFree(g_ws_ptr[dev]);
+      g_ws_ptr[dev] = nullptr;
+      g_ws_bytes[dev] = 0;
+    }
+    void* ptr = nullptr;
+    hipError_t e = hipMalloc(&ptr, need);
+    if (e != hipSuccess) return fail(DA_ERR_WORKSPACE, "hipMalloc(%zu) failed: %s", need, hipGetErrorString(e));
+    g_ws_ptr[dev] = ptr;
+    g_ws_bytes[dev] = need;
+  }
+  *out = (uint8_t*)g_ws_ptr[dev];
+  return DA_OK;
+}
+
+int check_launch(hipError_t e, const char* what) {
+  if (e != hipSuccess) return fail(DA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return DA_OK;
+}
+
+int attention(const void* q, const void* k, const void* v, void* o, const da_params* p, bool distr) {
+  Resolved r;
+  int rc = resolve(p, distr, &r);
+  if (rc) return rc;
+  rc = check_tensors(q, k, v, o);
+  if (rc) return rc;
+  if (r.dtype == DA_BF16 && !da::attn_bf16_supported(r.pb, distr ? 1 : 0))
+    return fail(DA_ERR_UNSUPPORTED, "bf16 kernels need n_groups in {16, 32, 64, 128} (a multiple of the MFMA step) "
+                "and at least 4 groups per wavefront; got d=%d Br=%d n_groups=%d", p->d, p->Br, p->n_groups);
+  uint8_t* perm = nullptr;
+  if (distr) {
+    rc = get_perm_buffer(p, r, &perm);
+    if (rc) return rc;
+    rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, perm, p->hash_out, r.stream), "lsh_group launch");
+    if (rc) return rc;
+  }
+  hipError_t e = (r.dtype == DA_BF16)
+                     ? da::launch_attn_bf16(q, k, v, o, perm, r.pb, distr ? 1 : 0, r.stream)
+                     : da::launch_attn_f32(q, k, v, o, perm, r.pb, distr ? 1 : 0, r.stream);
+  return check_launch(e, "attention launch");
+}
+
+da_params short_form(int B, int H, int Hkv, int N, int d, int Br, int Bc, int n_groups, uint64_t seed, int causal) {
+  da_params p = {};
+  p.B = B; p.H = H; p.Hkv = Hkv; p.N = N; p.d = d; p.Br = Br; p.Bc = Bc;
+  p.n_groups = n_groups; p.causal = causal; p.lsh_seed = seed;
+  p.dtype = DA_BF16;
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int distr_attn_fwd(const void* q, const void* k, const void* v, void* o, int B, int H, int Hkv, int N,
+                   int d, int Br, int Bc, int n_groups, uint64_t lsh_seed, int causal) {
+  da_params p = short_form(B, H, Hkv, N, d, Br, Bc, n_groups, lsh_seed, causal);
+  return attention(q, k, v, o, &p, true);
+}
+
+int distr_attn_exact_fwd(const void* q, const void* k, const void* v, void* o, int B, int H, int Hkv,
+                         int N, int d, int Br, int Bc, int causal) {
+  da_params p = short_form(B, H, Hkv, N, d, Br, Bc, d, 0, causal);
+  return attention(q, k, v, o, &p, false);
+}
+
+int distr_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, const da_params* p) {
+  return attention(q, k, v, o, p, true);
+}
+
+int distr_attn_exact_fwd_ex(const void* q, const void* k, const void* v, void* o, const da_params* p) {
+  return attention(q, k, v, o, p, false);
+}
+
+int distr_attn_lsh_group(const void* q, const da_params* p) {
+  Resolved r;
+  int rc = resolve(p, true, &r);
+  if (rc) return rc;
+  if (!q) return fail(DA_ERR_INVALID_ARG, "q must be non-null");
+  if (!p->perm_out && !p->hash_out) return fail(DA_ERR_INVALID_ARG, "perm_out or hash_out must be given");
+  return check_launch(da::launch_lsh_group(q, r.dtype, r.pb, p->perm_out, p->hash_out, r.stream), "lsh_group launch");
+}
+
+size_t distr_attn_workspace_bytes(const da_params* p) {
+  Resolved r;
+  if (resolve(p, true, &r)) return 0;
+  return perm_bytes(r);
+}
+
+int distr_attn_hyperplanes(uint64_t seed, int n_planes, int Br, float* host_out) {
+  if (!host_out || n_planes < 1 || n_planes > da::kMaxPlanes || Br < 1)
+    return fail(DA_ERR_INVALID_ARG, "hyperplanes: bad arguments");
+  for (int p = 0; p < n_planes; ++p)
+    for (int r = 0; r < Br; ++r)
+      host_out[(size_t)p * Br + r] = da::hyperplane_entry(seed, (uint32_t)p, (uint32_t)r);
+  return DA_OK;
+}
+
+int distr_attn_set_stream(void* hip_stream) {
+  g_stream.store(hip_stream);
+  return DA_OK;
+}
+
+int distr_attn_release(void) {
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  int rc = DA_OK;
+  int cur = 0;
+  bool have_cur = hipGetDevice(&cur) == hipSuccess;
+  for (int dev = 0; dev < 16; ++dev) {
+    if (!g_ws_ptr[dev]) continue;
+    if (hipSetDevice(dev) != hipSuccess || hipDeviceSynchronize() != hipSuccess || hipFree(g_ws_ptr[dev]) != hipSuccess)
+      rc = fail(DA_ERR_HIP, "release: freeing the workspace of device %d failed", dev);
+    g_ws_ptr[dev] = nullptr;
+    g_ws_bytes[dev] = 0;
+  }
+  if (have_cur) (void)hipSetDevice(cur);
+  return rc;
+}
+
+const char* distr_attn_last_error(void) { return g_err; }
+
+const char* distr_attn_version(void) { return "distr_attn 0.1 (gfx950)"; }
+
+}  // extern "C"

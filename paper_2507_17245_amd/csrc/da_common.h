@@ -1,0 +1,50 @@
+// Shared declarations of the gfx950 DistrAttention library (device helpers + kernel launchers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace da {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+constexpr int kBc = 64;          // key/value rows per tile (the paper's m)
+constexpr int kMaxPlanes = 32;   // sign bits per hash
+
+// Projection matrix entry (plane p, row r) of the LSH stage (Sec. 3.2: a fixed random matrix).
+// Counter-based: mix a 64-bit counter, add its four 16-bit fields, centre. The value is an
+// integer in [-131070, 131070] times 2^-16, so float holds it exactly on host and device.
+__host__ __device__ inline float hyperplane_entry(uint64_t seed, uint32_t p, uint32_t r) {
+  uint64_t z = seed + 0x9E3779B97F4A7C15ULL * (((uint64_t)p << 32) + (uint64_t)r + 1ULL);
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+  z ^= z >> 31;
+  int sum = (int)(z & 0xFFFF) + (int)((z >> 16) & 0xFFFF) + (int)((z >> 32) & 0xFFFF) + (int)(z >> 48);
+  return (float)(sum - 131070) * (1.0f / 65536.0f);
+}
+
+struct Problem {
+  int B, H, Hkv, N, d, Br, n_groups, causal, n_planes, gray_mode;
+  uint64_t seed;
+  float scale;
+};
+
+// Launchers (defined next to their kernels). All return hipError_t of the launch.
+hipError_t launch_lsh_group(const void* q, int dtype, const Problem& pb, uint8_t* perm_out,
+                            uint32_t* hash_out, hipStream_t stream);
+// distr != 0: S^ = Q_r K_f^T with the per-block permutation table `perm` [B][H][Tq][d].
+hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
+                            const Problem& pb, int distr, hipStream_t stream);
+hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
+                           const Problem& pb, int distr, hipStream_t stream);
+bool attn_bf16_supported(const Problem& pb, int distr);
+
+}  // namespace da

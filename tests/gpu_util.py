@@ -1,0 +1,67 @@
+"""Helpers of the GPU parity tests: host arrays -> device tensors, one call through the C ABI,
+results back as numpy. No arithmetic of the method lives here."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2507_17245_amd as da
+
+BF16_MAX_ABS, BF16_MEAN_ABS, F32_MAX_ABS = 2e-2, 2e-3, 1e-4   # tolerances of the parity bar
+
+
+def to_dev(x, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    return t.to(torch.bfloat16) if dtype == "bf16" else t     # exact: values are bf16-representable
+
+
+def run_gpu(cfg, q, k, v, distr=True, want_tables=False, n_groups=None, lsh_seed=None, gray_mode=0):
+    """One forward through the C ABI. -> (o float64 numpy, perm uint8 or None, hash uint32 or None)."""
+    tq, tk, tv = (to_dev(x, cfg.dtype) for x in (q, k, v))
+    o = torch.full_like(tq, float("nan"))
+    perm = hsh = None
+    if want_tables:
+        perm = torch.zeros((cfg.B, cfg.H, cfg.Tq, cfg.d), dtype=torch.uint8, device="cuda")
+        hsh = torch.zeros((cfg.B, cfg.H, cfg.Tq, cfg.d), dtype=torch.int32, device="cuda")
+    p = da.make_params(tq, tk, tv, Br=cfg.Br, Bc=cfg.Bc,
+                       n_groups=cfg.n_groups if n_groups is None else n_groups, causal=cfg.causal,
+                       lsh_seed=cfg.lsh_seed if lsh_seed is None else lsh_seed,
+                       n_planes=cfg.n_planes, gray_mode=gray_mode, perm_out=perm, hash_out=hsh)
+    if distr:
+        da.distr_attn_fwd_ex(tq, tk, tv, o, p)
+    else:
+        da.distr_attn_exact_fwd_ex(tq, tk, tv, o, p)
+    torch.cuda.synchronize()
+    o_np = o.float().cpu().numpy().astype(np.float64)
+    if want_tables:
+        return o_np, perm.cpu().numpy(), hsh.cpu().numpy().view(np.uint32)
+    return o_np, None, None
+
+
+def run_gpu_lsh(cfg, q, gray_mode=0):
+    tq = to_dev(q, cfg.dtype)
+    perm = torch.zeros((cfg.B, cfg.H, cfg.Tq, cfg.d), dtype=torch.uint8, device="cuda")
+    hsh = torch.zeros((cfg.B, cfg.H, cfg.Tq, cfg.d), dtype=torch.int32, device="cuda")
+    p = da.make_params(tq, tq, tq, Br=cfg.Br, Bc=cfg.Bc, n_groups=cfg.n_groups, causal=cfg.causal,
+                       lsh_seed=cfg.lsh_seed, n_planes=cfg.n_planes, gray_mode=gray_mode,
+                       perm_out=perm, hash_out=hsh)
+    da.distr_attn_lsh_group(tq, p)
+    torch.cuda.synchronize()
+    return perm.cpu().numpy(), hsh.cpu().numpy().view(np.uint32)
+
+
+def oracle_params(cfg, n_groups=None, lsh_seed=None, gray_mode=0):
+    return oracle.params(cfg.B, cfg.H, cfg.Hkv, cfg.N, cfg.d, cfg.Br,
+                         cfg.n_groups if n_groups is None else n_groups, causal=cfg.causal,
+                         n_planes=cfg.n_planes, gray_mode=gray_mode,
+                         lsh_seed=cfg.lsh_seed if lsh_seed is None else lsh_seed)
+
+
+def assert_close(got, want, dtype, what=""):
+    err = np.abs(got - want)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    if dtype == "bf16":
+        assert err.max() <= BF16_MAX_ABS, f"{what}: max-abs {err.max():.4g}"
+        assert err.mean() <= BF16_MEAN_ABS, f"{what}: mean-abs {err.mean():.4g}"
+    else:
+        assert err.max() <= F32_MAX_ABS, f"{what}: max-abs {err.max():.4g}"
+    return float(err.max()), float(err.mean())

@@ -1,0 +1,103 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every declared
+symbol, rejects bad arguments before touching a device, and its projection-matrix generator
+agrees with the oracle's independently written one."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2507_17245_amd as da
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "distr_attn.h")).read()
+    declared = set(re.findall(r"\b(distr_attn_\w+)\s*\(", header))
+    assert declared == set(da.EXPORTS)
+    L = da.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert "gfx950" in da.distr_attn_version()
+
+
+def test_struct_layout_matches_header_order():
+    header = open(os.path.join(ROOT, "include", "distr_attn.h")).read()
+    body = header[header.index("typedef struct {"):header.index("} da_params;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for decl in body.split("{", 1)[1].split(";"):
+        decl = decl.strip()
+        if not decl:
+            continue
+        for part in decl.split(","):
+            names.append(re.findall(r"(\w+)\s*$", part.strip())[0])
+    assert names == [f[0] for f in da.DaParams._fields_]
+
+
+def test_hyperplanes_match_the_oracle_generator():
+    for seed, planes, Br in [(0, 16, 128), (7, 4, 64), (2 ** 63 + 5, 32, 128), (123456789, 1, 1)]:
+        assert np.array_equal(da.distr_attn_hyperplanes(seed, planes, Br), oracle.hyperplanes(seed, planes, Br))
+
+
+def _params(**kw):
+    base = dict(B=1, H=4, Hkv=2, N=100, d=64, Br=64, Bc=64, n_groups=32, causal=0, lsh_seed=0,
+                dtype=da.DA_BF16, n_planes=0, softmax_scale=0.0, gray_mode=0)
+    base.update(kw)
+    p = da.DaParams()
+    for k, v in base.items():
+        setattr(p, k, v)
+    return p
+
+
+FAKE = ctypes.c_void_p(0x1000)   # never dereferenced: every check below fails on the host first
+FAKE_O = ctypes.c_void_p(0x2000)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(B=0), da.DA_ERR_INVALID_ARG),
+    (dict(N=-3), da.DA_ERR_INVALID_ARG),
+    (dict(H=3, Hkv=2), da.DA_ERR_INVALID_ARG),
+    (dict(n_groups=24), da.DA_ERR_INVALID_ARG),          # 64 % 24 != 0: groups have a constant size
+    (dict(n_groups=0), da.DA_ERR_INVALID_ARG),
+    (dict(dtype=5), da.DA_ERR_INVALID_ARG),
+    (dict(causal=2), da.DA_ERR_INVALID_ARG),
+    (dict(gray_mode=3), da.DA_ERR_INVALID_ARG),
+    (dict(softmax_scale=-1.0), da.DA_ERR_INVALID_ARG),
+    (dict(d=96, n_groups=48), da.DA_ERR_UNSUPPORTED),
+    (dict(Br=32), da.DA_ERR_UNSUPPORTED),
+    (dict(Bc=128), da.DA_ERR_UNSUPPORTED),
+    (dict(n_planes=33), da.DA_ERR_UNSUPPORTED),
+    (dict(n_groups=8), da.DA_ERR_UNSUPPORTED),            # below the MFMA contraction step
+])
+def test_bad_arguments_fail_on_the_host(kw, code):
+    p = _params(**kw)
+    rc = da.lib().distr_attn_fwd_ex(FAKE, FAKE, FAKE, FAKE_O, ctypes.byref(p))
+    assert rc == code
+    assert da.lib().distr_attn_last_error()
+
+
+def test_pointer_checks():
+    L = da.lib()
+    p = _params()
+    assert L.distr_attn_fwd_ex(None, FAKE, FAKE, FAKE_O, ctypes.byref(p)) == da.DA_ERR_INVALID_ARG
+    assert L.distr_attn_fwd_ex(FAKE, FAKE, FAKE, FAKE, ctypes.byref(p)) == da.DA_ERR_INVALID_ARG      # o aliases q
+    assert L.distr_attn_fwd_ex(ctypes.c_void_p(0x1004), FAKE, FAKE, FAKE_O, ctypes.byref(p)) == da.DA_ERR_INVALID_ARG
+    assert L.distr_attn_exact_fwd_ex(FAKE, FAKE, FAKE, FAKE_O, None) == da.DA_ERR_INVALID_ARG
+    assert L.distr_attn_lsh_group(FAKE, ctypes.byref(p)) == da.DA_ERR_INVALID_ARG                     # no output given
+    assert L.distr_attn_fwd(FAKE, FAKE, FAKE, FAKE_O, 1, 4, 3, 64, 64, 64, 64, 32, 0, 0) == da.DA_ERR_INVALID_ARG
+    assert L.distr_attn_exact_fwd(FAKE, FAKE, FAKE, FAKE_O, 1, 4, 2, 64, 80, 64, 64, 0) == da.DA_ERR_UNSUPPORTED
+    assert L.distr_attn_hyperplanes(0, 16, 64, None) == da.DA_ERR_INVALID_ARG
+    # caller workspace too small
+    p = _params(workspace=0x3000, workspace_bytes=16)
+    assert L.distr_attn_fwd_ex(FAKE, FAKE, FAKE, FAKE_O, ctypes.byref(p)) == da.DA_ERR_WORKSPACE
+
+
+def test_workspace_bytes():
+    p = _params(B=2, H=4, Hkv=4, N=197, d=64, Br=64)
+    need = da.distr_attn_workspace_bytes(p)
+    assert need >= 2 * 4 * 4 * 64 and need % 256 == 0
+    assert da.distr_attn_workspace_bytes(_params(n_groups=7)) == 0
