@@ -61,6 +61,8 @@ typedef struct {
   size_t workspace_bytes;
   uint8_t *perm_out;    /* optional device [B][H][Tq][d]: channel at sorted position s of each block */
   uint32_t *hash_out;   /* optional device [B][H][Tq][d]: hash of each channel of each block          */
+  const uint8_t *perm_in; /* optional device [B][H][Tq][d]: use this grouping and skip the LSH stage
+                             (each row must be a permutation of 0..d-1; it is not checked)          */
 } da_params;
 
 /*

@@ -30,7 +30,7 @@ class DaParams(ctypes.Structure):
         ("n_planes", ctypes.c_int), ("softmax_scale", ctypes.c_float), ("gray_mode", ctypes.c_int),
         ("stream", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_size_t), ("perm_out", ctypes.c_void_p),
-        ("hash_out", ctypes.c_void_p),
+        ("hash_out", ctypes.c_void_p), ("perm_in", ctypes.c_void_p),
     ]
 
 
@@ -104,7 +104,8 @@ def _shapes(q, k, v):
 
 
 def make_params(q, k, v, Br, Bc=64, n_groups=None, causal=False, lsh_seed=0, n_planes=0,
-                softmax_scale=0.0, gray_mode=0, workspace=None, perm_out=None, hash_out=None):
+                softmax_scale=0.0, gray_mode=0, workspace=None, perm_out=None, hash_out=None,
+                perm_in=None):
     B, H, Hkv, N, d = _shapes(q, k, v)
     p = DaParams()
     p.B, p.H, p.Hkv, p.N, p.d, p.Br, p.Bc = B, H, Hkv, N, d, Br, Bc
@@ -121,6 +122,7 @@ def make_params(q, k, v, Br, Bc=64, n_groups=None, causal=False, lsh_seed=0, n_p
         p.workspace_bytes = workspace.numel() * workspace.element_size()
     p.perm_out = perm_out.data_ptr() if perm_out is not None else None
     p.hash_out = hash_out.data_ptr() if hash_out is not None else None
+    p.perm_in = perm_in.data_ptr() if perm_in is not None else None
     return p
 
 

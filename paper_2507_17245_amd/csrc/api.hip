@@ -126,12 +126,16 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
   if (r.dtype == DA_BF16 && !da::attn_bf16_supported(r.pb, distr ? 1 : 0))
     return fail(DA_ERR_UNSUPPORTED, "bf16 kernels need n_groups in {16, 32, 64, 128} (a multiple of the MFMA step) "
                 "and at least 4 groups per wavefront; got d=%d Br=%d n_groups=%d", p->d, p->Br, p->n_groups);
-  uint8_t* perm = nullptr;
-  if (distr) {
-    rc = get_perm_buffer(p, r, &perm);
+  const uint8_t* perm = nullptr;
+  if (distr && p->perm_in) {
+    perm = p->perm_in;
+  } else if (distr) {
+    uint8_t* table = nullptr;
+    rc = get_perm_buffer(p, r, &table);
     if (rc) return rc;
-    rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, perm, p->hash_out, r.stream), "lsh_group launch");
+    rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, table, p->hash_out, r.stream), "lsh_group launch");
     if (rc) return rc;
+    perm = table;
   }
   hipError_t e = (r.dtype == DA_BF16)
                      ? da::launch_attn_bf16(q, k, v, o, perm, r.pb, distr ? 1 : 0, r.stream)
