@@ -103,7 +103,7 @@ int distr_attn_hyperplanes(uint64_t seed, int n_planes, int Br, float *host_out)
 /* Stream used when da_params.stream is NULL and by the short-form entry points (process-wide). */
 int distr_attn_set_stream(void *hip_stream);
 
-/* Frees library-owned device memory (workspace, cached projection matrices). */
+/* Frees the library-owned device workspace (synchronises the device first). */
 int distr_attn_release(void);
 
 const char *distr_attn_last_error(void);
