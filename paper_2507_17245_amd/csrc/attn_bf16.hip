@@ -82,16 +82,23 @@ struct Cfg {
   static constexpr int G = D / KRED;              // channels per group
   static constexpr int CH = D / 8;                // 16-byte chunks per row
   static constexpr int CPT = kBc * CH / T;        // chunks each thread stages per tile
-  // LDS row strides in elements. Raw K of the distr path is only read by 2-byte gathers down a
-  // column: an odd number of dwords per row keeps 64 rows on distinct banks. Rows read by
-  // 16-byte accesses need 16-byte alignment; +8 elements shifts consecutive rows by 4 banks.
-  // V is read by transposing 8-byte accesses, 4 rows x 64 bytes per half wave: +32 elements.
-  static constexpr int KS = DISTR ? D + 2 : D + 8;
-  static constexpr int KFS = KRED + 8;
+  // LDS row strides in elements. Rows read by 16-byte accesses need 16-byte alignment; +8
+  // elements shifts consecutive rows by 4 banks. V is read by transposing 8-byte accesses,
+  // 4 rows x 64 bytes per half wave: +32 elements. The raw K tile of the distr path is only
+  // read by 2-byte gathers down a column: an odd number of dwords per row keeps the 64 rows of
+  // a wave on distinct banks.
+  static constexpr int KXS = KRED + 8;            // Kx tile: K (exact) or K_f (distr)
+  static constexpr int KRS = D + 2;               // raw K tile (distr only)
   static constexpr int VS = D + 32;
   static constexpr int SP = KRED / NW;            // fused slots each wave builds per key row
   static constexpr int NGATHER = SP * G;          // 2-byte gathers per lane per tile (= D / NW)
+  static constexpr int KSTEPS = KRED / 16;        // MFMA steps of the score product
 };
+
+// Rows whose running maximum moved by less than this (in log2 units) keep their old reference
+// maximum: P is then at most 2^kTau, the sums stay exact ratios, and the accumulator rescale
+// (one multiply per accumulator register) is skipped for almost every tile.
+constexpr float kTau = 8.0f;
 
 template <int D, int BR, int KRED, bool DISTR>
 __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
@@ -99,9 +106,14 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
     bf16* __restrict__ o, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Tq,
     int causal, float scale_log2e, int total_units) {
   using C = Cfg<D, BR, KRED, DISTR>;
-  __shared__ __attribute__((aligned(16))) bf16 k_lds[kBc * C::KS];
-  __shared__ __attribute__((aligned(16))) bf16 v_lds[kBc * C::VS];
-  __shared__ __attribute__((aligned(16))) f16 kf_lds[DISTR ? kBc * C::KFS : 8];
+  using kx_t = typename std::conditional<DISTR, f16, bf16>::type;
+  using kx8 = typename std::conditional<DISTR, f16x8, bf16x8>::type;
+  constexpr int KX_BUF = kBc * C::KXS;   // elements per Kx buffer
+  constexpr int V_BUF = kBc * C::VS;
+  // Kx and V tiles are double-buffered: while tile i multiplies, tile i+1 (V) / i+2 (K) lands.
+  __shared__ __attribute__((aligned(16))) kx_t kx_lds[2 * KX_BUF];
+  __shared__ __attribute__((aligned(16))) bf16 v_lds[2 * V_BUF];
+  __shared__ __attribute__((aligned(16))) bf16 kraw_lds[DISTR ? kBc * C::KRS : 8];
   __shared__ uint8_t perm_lds[DISTR ? D : 4];
 
   const int tid = threadIdx.x;
@@ -141,90 +153,81 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
   // exactly (8 vs 11 significand bits) inside half's exponent range, and the fused keys, rounded
   // once from their float sum, keep 3 more bits than bf16 would: with bf16 K_f the logit error
   // on inputs with heavy-tailed channel scales exceeds what the output tolerance allows.
-  using kx8 = typename std::conditional<DISTR, f16x8, bf16x8>::type;
-  kx8 qop[KRED / 16];
+  kx8 qop[C::KSTEPS];
   if constexpr (DISTR) {
     const bf16* qrow = qh + (size_t)q_ld * D;
 #pragma unroll
-    for (int s = 0; s < KRED / 16; ++s) {
+    for (int s = 0; s < C::KSTEPS; ++s) {
 #pragma unroll
       for (int j = 0; j < 8; ++j)
         qop[s][j] = to_half_sat((float)qrow[perm_lds[(16 * s + 8 * hh + j) * C::G]]);
     }
   } else {
 #pragma unroll
-    for (int s = 0; s < KRED / 16; ++s)
+    for (int s = 0; s < C::KSTEPS; ++s)
       qop[s] = *(const bf16x8*)(qh + (size_t)q_ld * D + 16 * s + 8 * hh);
   }
+  // The Q operands must have landed before the loop starts: otherwise the compiler's wait-count
+  // bookkeeping carries "Q loads pending" into the loop and the MFMAs also wait for the K/V
+  // prefetch of later tiles.
+#pragma unroll
+  for (int s = 0; s < C::KSTEPS; ++s) asm volatile("" : "+v"(qop[s]));
 
-  // ---- fusion gather offsets (bytes into k_lds), fixed for the Q block ----------------------
-  // Thread (row n = tid % 64, part = wave) builds K_f[n][part*SP .. part*SP+SP-1].
+  // ---- fusion gather offsets (bytes into kraw_lds), fixed for the Q block -------------------
+  // Thread (row n = lane, part = wave) builds K_f[n][part*SP .. part*SP+SP-1].
   int goff[DISTR ? C::NGATHER : 1];
   if constexpr (DISTR) {
 #pragma unroll
     for (int i = 0; i < C::NGATHER; ++i)
-      goff[i] = (lane * C::KS + perm_lds[wave * C::NGATHER + i]) * 2;
+      goff[i] = (lane * C::KRS + perm_lds[wave * C::NGATHER + i]) * 2;
   }
 
-  // ---- staging registers: global -> registers -> LDS -----------------------------------------
+  const int n_end = causal ? min(N, r0 + BR) : N;
+  const int n_tiles = (n_end + kBc - 1) / kBc;
+  // tiles [0, n_full) need no masking for any row of the block
+  const int n_full = causal ? min(r0, N) / kBc : N / kBc;
+
+  // ---- staging: global -> registers -> LDS ---------------------------------------------------
+  // K and V rows are fetched through buffer descriptors: the per-lane byte offset inside a
+  // tile is fixed, the tile advances through the scalar offset, and rows past the end of the
+  // head read as zero (hardware range check), so a tile costs no address arithmetic.
   u32x4 kst[C::CPT], vst[C::CPT];
-  auto stage_load = [&](int n0) {
+  const unsigned head_bytes = (unsigned)N * D * 2;
+  const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kh, 0, head_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)vh, 0, head_bytes, 0x00020000);
+  const int st_voff = ((tid / C::CH) * D + (tid % C::CH) * 8) * 2;   // chunk j adds j * (T / CH) rows
+  auto load_rows = [&](__amdgpu_buffer_rsrc_t rsrc, int tile, u32x4 (&st)[C::CPT]) {
+    const int soff = tile * (kBc * D * 2);
+#pragma unroll
+    for (int j = 0; j < C::CPT; ++j)
+      st[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, st_voff + j * (C::T / C::CH) * D * 2, soff, 0);
+  };
+  auto store_v = [&](int buf) {
 #pragma unroll
     for (int j = 0; j < C::CPT; ++j) {
       int id = tid + j * C::T;
-      int row = min(n0 + id / C::CH, N - 1);
-      int col = (id % C::CH) * 8;
-      kst[j] = *(const u32x4*)(kh + (size_t)row * D + col);
-      vst[j] = *(const u32x4*)(vh + (size_t)row * D + col);
+      *(u32x4*)(v_lds + buf * V_BUF + (id / C::CH) * C::VS + (id % C::CH) * 8) = vst[j];
     }
   };
-  auto stage_store = [&]() {
+  auto store_k = [&](int buf) {   // exact: K tile as it is; distr: raw tile for the gathers
 #pragma unroll
     for (int j = 0; j < C::CPT; ++j) {
       int id = tid + j * C::T;
       int row = id / C::CH, col = (id % C::CH) * 8;
       if constexpr (DISTR) {
-        unsigned* dst = (unsigned*)(k_lds + row * C::KS + col);
+        unsigned* dst = (unsigned*)(kraw_lds + row * C::KRS + col);
         dst[0] = kst[j][0]; dst[1] = kst[j][1]; dst[2] = kst[j][2]; dst[3] = kst[j][3];
       } else {
-        *(u32x4*)(k_lds + row * C::KS + col) = kst[j];
+        *(u32x4*)(kx_lds + buf * KX_BUF + row * C::KXS + col) = kst[j];
       }
-      *(u32x4*)(v_lds + row * C::VS + col) = vst[j];
     }
   };
-
-  // ---- accumulators and softmax state ---------------------------------------------------------
-  f32x16 oacc[D / 32];
-#pragma unroll
-  for (int mb = 0; mb < D / 32; ++mb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) oacc[mb][i] = 0.0f;
-  float m_run = -INFINITY;   // running row max, in log2 units (already scaled)
-  float l_run = 0.0f;        // running row sum over this lane's half of the keys
-
-  const int n_end = causal ? min(N, r0 + BR) : N;
-  const int n_tiles = (n_end + kBc - 1) / kBc;
-
-  // LDS addresses that do not change across tiles
-  using kx_t = typename std::conditional<DISTR, f16, bf16>::type;
-  const kx_t* ka_base;
-  if constexpr (DISTR) ka_base = kf_lds + lq * C::KFS + 8 * hh;
-  else ka_base = k_lds + lq * C::KS + 8 * hh;
-  const bf16* vt_base = v_lds + (((lane & 15) >> 2) + 4 * hh) * C::VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-
-  stage_load(0);
-  stage_store();
-  __syncthreads();
-
-  for (int it = 0; it < n_tiles; ++it) {
-    const int n0 = it * kBc;
-    if (it + 1 < n_tiles) stage_load(n0 + kBc);
-
+  // ---- fusion (Sec. 3.2): K_f[n][j] = sum of the group's key channels, in float, rounded to
+  // half once. Two members are gathered into one register and summed by a bf16 dot product
+  // with (1, 1).
+  auto fuse = [&](int buf) {
     if constexpr (DISTR) {
-      // ---- fusion (Sec. 3.2): K_f[n][j] = sum of the group's key channels, in float, rounded
-      // to half once. The two members of a pair are gathered into one register and summed by a
-      // bf16 dot product with (1, 1).
-      const char* kraw = (const char*)k_lds;
+      const char* kraw = (const char*)kraw_lds;
       const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
       f16 fused[C::SP];
 #pragma unroll
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
           fused[sl] = to_half_sat(acc);
         }
       }
-      f16* dst = kf_lds + lane * C::KFS + wave * C::SP;
+      f16* dst = (f16*)kx_lds + buf * KX_BUF + lane * C::KXS + wave * C::SP;
       if constexpr (C::SP % 8 == 0) {
 #pragma unroll
         for (int c8 = 0; c8 < C::SP / 8; ++c8) {
@@ -252,86 +255,204 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
           *(f16x8*)(dst + c8 * 8) = pk;
         }
       } else {
-        static_assert(C::SP == 4, "fused slots per wave must be 4 or a multiple of 8");
+        static_assert(!DISTR || C::SP % 8 == 0 || C::SP == 4, "fused slots per wave: 4 or a multiple of 8");
         f16x4 pk = {fused[0], fused[1], fused[2], fused[3]};
         *(f16x4*)dst = pk;
       }
-      __syncthreads();
     }
+  };
 
-    // wave-uniform: does this wave see any key of the tile, and does it need masking?
-    const bool wave_active = !causal || n0 <= qw0 + 31;
-    if (wave_active) {
-      // ---- S^T = Kx . Qx^T ---------------------------------------------------------------------
-      f32x16 sacc[2];
+  // ---- accumulators and softmax state ---------------------------------------------------------
+  f32x16 oacc[D / 32];
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
+  for (int mb = 0; mb < D / 32; ++mb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[mb][i] = 0.0f;
+    for (int i = 0; i < 16; ++i) oacc[mb][i] = 0.0f;
+  float m_ref = -INFINITY;   // reference row max, log2 units (scaled); at most kTau below the true max
+  float l_run = 0.0f;        // row sum over this lane's half of the keys, relative to m_ref
+
+  // LDS addresses of this lane's operands inside buffer 0
+  const kx_t* ka_base = kx_lds + lq * C::KXS + 8 * hh;
+  const bf16* vt_base = v_lds + (((lane & 15) >> 2) + 4 * hh) * C::VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+
+  // S^T = Kx . Qx^T for the Kx tile in buffer `buf`: register i of block mb holds key
+  // 32*mb + 8*(i/4) + 4*hh + i%4 of the tile.
+  auto qk = [&](int buf, f32x16 (&sacc)[2]) {
+    const kx_t* base = ka_base + buf * KX_BUF;
 #pragma unroll
-        for (int s = 0; s < KRED / 16; ++s) {
-          kx8 a = *(const kx8*)(ka_base + mb * 32 * (DISTR ? C::KFS : C::KS) + 16 * s);
-          sacc[mb] = mfma_32x32x16(a, qop[s], sacc[mb]);
-        }
+    for (int mb = 0; mb < 2; ++mb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[mb][i] = 0.0f;
+#pragma unroll
+      for (int s = 0; s < C::KSTEPS; ++s) {
+        kx8 a = *(const kx8*)(base + mb * 32 * C::KXS + 16 * s);
+        sacc[mb] = mfma_32x32x16(a, qop[s], sacc[mb]);
       }
-      // register i of block mb holds key  n0 + 32*mb + 8*(i/4) + 4*hh + i%4
-      const bool need_mask = (n0 + kBc > N) || (causal && n0 + kBc - 1 > qw0);
-      if (need_mask) {
-        const int lim = causal ? min(q_abs, N - 1) : N - 1;  // last visible key of this row
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            int kv = n0 + 32 * mb + 8 * (i >> 2) + 4 * hh + (i & 3);
-            if (kv > lim) sacc[mb][i] = -INFINITY;
-          }
-      }
-      // ---- online softmax ---------------------------------------------------------------------
-      float mt = sacc[0][0];
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sacc[mb][i]);
-      mt = half_swap_max(mt);
-      const float m_new = fmaxf(m_run, mt * scale_log2e);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
-      float rs = 0.0f;
-      bf16x8 pop[4];
+    }
+  };
+
+  // Softmax bookkeeping for the scores `sc` of tile `tile`, before they are exponentiated: mask,
+  // row maximum, and -- only when some row's maximum ran more than kTau ahead of its reference --
+  // a new reference with the matching rescale of the row sum and of the output accumulator.
+  auto row_max = [&](auto mask_c, int tile, f32x16 (&sc)[2]) -> float {
+    if constexpr (decltype(mask_c)::value) {
+      const int lim = causal ? min(q_abs, N - 1) : N - 1;  // last visible key of this row
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[mb][i], scale_log2e, -m_new));
-          rs += p;
-          pop[mb * 2 + (i >> 3)][i & 7] = (bf16)p;
+          int kv = tile * kBc + 32 * mb + 8 * (i >> 2) + 4 * hh + (i & 3);
+          if (kv > lim) sc[mb][i] = -INFINITY;
         }
-      l_run = l_run * alpha + rs;
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+    }
+    float mt = sc[0][0];
 #pragma unroll
-        for (int mb = 0; mb < D / 32; ++mb)
+    for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[mb][i] *= alpha;
-      }
-      // ---- O^T += V^T . P^T ---------------------------------------------------------------------
-      // step tt covers the 16 keys n0 + 16*tt + {8*(j/4) + 4*hh + j%4}: rows 16*tt + 4*hh + 0..3
-      // and 16*tt + 8 + 4*hh + 0..3 of the V tile.
+      for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sc[mb][i]);
+    return half_swap_max(mt) * scale_log2e;
+  };
+  auto move_reference = [&](float mt) {
+    const bool moved = mt > m_ref + kTau;
+    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+      const float m_new = moved ? mt : m_ref;
+      const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // exp2(-inf) = 0 on the first tile
+      m_ref = m_new;
+      l_run *= alpha;
 #pragma unroll
-      for (int tt = 0; tt < 4; ++tt) {
+      for (int mb = 0; mb < D / 32; ++mb)
 #pragma unroll
-        for (int mb = 0; mb < D / 32; ++mb) {
-          const bf16* p0 = vt_base + (16 * tt) * C::VS + 32 * mb;
-          bf16x8 a = lds_read_tr_pair(p0, p0 + 8 * C::VS);
-          oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pop[tt], oacc[mb], 0, 0, 0);
+        for (int i = 0; i < 16; ++i) oacc[mb][i] *= alpha;
+    }
+  };
+
+  // One tile `it`, whose scores `sc` already went through row_max / move_reference:
+  //   phase X: scores of tile it+1 into `sn` (matrix pipe)  ||  exp, bf16 P, row sum of `sc` (vector ALUs)
+  //   phase Y: O^T += V^T . P^T for tile it (matrix pipe)    ||  mask and row maximum of `sn` (vector ALUs)
+  // then the rare reference move for tile it+1, the LDS stores of the prefetched tiles, one barrier.
+  // The scheduling hints at the end ask the compiler to interleave the two instruction streams
+  // instead of emitting them one after the other.
+  auto body = [&](auto mask_next_c, auto next_c, int it, int par, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
+    constexpr bool HAS_NEXT = decltype(next_c)::value;
+    if constexpr (HAS_NEXT) {
+      load_rows(k_rsrc, it + 2, kst);
+      load_rows(v_rsrc, it + 1, vst);
+    }
+    if constexpr (HAS_NEXT) qk(par ^ 1, sn);
+    // The row sum is taken over the bf16-rounded P, the values P.V really uses (one bf16 dot
+    // product with (1, 1) per register pair): numerator and denominator then carry the same
+    // rounding, which cancels for rows dominated by few keys.
+    bf16x8 pop[4];
+    {
+      const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
+      float rs0 = 0.0f, rs1 = 0.0f;
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mb][i], scale_log2e, -m_ref));
+          float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mb][i + 1], scale_log2e, -m_ref));
+          bf16x2 pr = {(bf16)p0, (bf16)p1};
+          pop[mb * 2 + (i >> 3)][i & 7] = pr[0];
+          pop[mb * 2 + (i >> 3)][(i & 7) + 1] = pr[1];
+          if (i & 2) rs1 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs1, false);
+          else rs0 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs0, false);
         }
+      l_run += rs0 + rs1;
+    }
+    // ---- O^T += V^T . P^T: step tt covers keys 16*tt + {8*(j/4) + 4*hh + j%4} of the tile,
+    // i.e. V rows 16*tt + 4*hh + 0..3 and 16*tt + 8 + 4*hh + 0..3.
+    const bf16* vb = vt_base + par * V_BUF;
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+#pragma unroll
+      for (int mb = 0; mb < D / 32; ++mb) {
+        const bf16* p0 = vb + (16 * tt) * C::VS + 32 * mb;
+        bf16x8 a = lds_read_tr_pair(p0, p0 + 8 * C::VS);
+        oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pop[tt], oacc[mb], 0, 0, 0);
       }
     }
-    __syncthreads();   // every wave is done reading this tile
-    if (it + 1 < n_tiles) {
-      stage_store();
+    float mt_next = 0.0f;
+    if constexpr (HAS_NEXT) mt_next = row_max(mask_next_c, it + 1, sn);
+    // ---- scheduling hints (groups are filled in this order) -----------------------------------
+    // One MFMA occupies the issue port for 8 cycles and the matrix pipe for 32: up to 6 vector
+    // instructions fit beside it. Operands are fetched from LDS four MFMAs ahead.
+    {
+      constexpr int N_QK = HAS_NEXT ? 2 * C::KSTEPS : 0;
+      constexpr int N_PV = D / 8;
+      constexpr int VALU_PER_MFMA = (150 + N_QK + N_PV - 1) / (N_QK + N_PV);
+      __builtin_amdgcn_sched_group_barrier(0x100, HAS_NEXT ? 4 : 8, 0);
+#pragma unroll
+      for (int i = 0; i < N_QK - 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one score MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        // a K operand, four MFMAs ahead
+        __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER_MFMA, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < (N_QK < 4 ? N_QK : 4); ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one score MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);        // K operands are all in: first V operands
+        __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER_MFMA, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < N_PV; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one P.V MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);        // next V operand
+        __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER_MFMA, 0);
+      }
+    }
+    if constexpr (HAS_NEXT) {
+      move_reference(mt_next);
+      // ---- land the prefetched tiles: V(it+1) and K(it+2) (buffers whose readers are done) ----
+      store_v(par ^ 1);
+      store_k(par);
+      if constexpr (DISTR) {
+        __syncthreads();
+        fuse(par);
+      }
+    }
+    __syncthreads();
+  };
+
+  // ---- prologue: tiles 0 (K, V) and 1 (K) into LDS, scores of tile 0 ---------------------------
+  load_rows(k_rsrc, 0, kst);
+  load_rows(v_rsrc, 0, vst);
+  store_k(0);
+  store_v(0);
+  if constexpr (DISTR) {
+    __syncthreads();
+    fuse(0);
+    __syncthreads();
+  }
+  if (n_tiles > 1) {
+    load_rows(k_rsrc, 1, kst);
+    store_k(1);
+    if constexpr (DISTR) {
       __syncthreads();
+      fuse(1);
     }
   }
+  __syncthreads();
+
+  const std::true_type yes;
+  const std::false_type no;
+  f32x16 s0[2], s1[2];
+  qk(0, s0);
+  move_reference(row_max(yes, 0, s0));
+
+  // Tile it+1 needs no mask while it+1 < n_full. The main loop is unrolled by two so that the
+  // two score register sets swap roles without copies.
+  int it = 0;
+  for (; it + 2 < n_full; it += 2) {
+    body(no, yes, it, 0, s0, s1);
+    body(no, yes, it + 1, 1, s1, s0);
+  }
+  for (; it < n_tiles - 1; ++it) {   // at most two unmasked leftovers plus the masked tiles
+    body(yes, yes, it, it & 1, s0, s1);
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) s0[mb] = s1[mb];
+  }
+  body(no, no, it, it & 1, s0, s1);
 
   // ---- epilogue: O = O_acc / l, bf16, 8-byte stores ---------------------------------------------
   const float l_tot = half_swap_sum(l_run);
