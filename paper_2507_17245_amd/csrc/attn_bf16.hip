@@ -82,18 +82,41 @@ struct Cfg {
   static constexpr int G = D / KRED;              // channels per group
   static constexpr int CH = D / 8;                // 16-byte chunks per row
   static constexpr int CPT = kBc * CH / T;        // chunks each thread stages per tile
-  // LDS row strides in elements. Rows read by 16-byte accesses need 16-byte alignment; +8
-  // elements shifts consecutive rows by 4 banks. V is read by transposing 8-byte accesses,
-  // 4 rows x 64 bytes per half wave: +32 elements. The raw K tile of the distr path is only
-  // read by 2-byte gathers down a column: an odd number of dwords per row keeps the 64 rows of
-  // a wave on distinct banks.
-  static constexpr int KXS = KRED + 8;            // Kx tile: K (exact) or K_f (distr)
-  static constexpr int KRS = D + 2;               // raw K tile (distr only)
-  static constexpr int VS = D + 32;
+  // LDS layouts.
+  //  * V tiles, and K tiles of the exact path, arrive by direct global->LDS loads (each
+  //    wave-level load drops 64 x 16 bytes contiguously), so rows are unpadded (D*2 bytes) and
+  //    bank conflicts are avoided by swizzling where a 16-byte chunk sits inside its row:
+  //      K (read with 16-byte accesses, 16 lanes = 16 rows at one logical chunk):
+  //          chunk' = chunk ^ (row & 15)            (D = 128: 16 chunks per row)
+  //          chunk' = chunk ^ ((row >> 1) & 7)      (D = 64: 8 chunks per row, two rows per 256 B)
+  //      V (read with transposing 8-byte accesses, 4 rows x 32 bytes per 16 lanes):
+  //          32-byte segment' = segment ^ (row & 7)         (D = 128)
+  //          32-byte segment' = segment ^ ((row >> 1) & 3)  (D = 64)
+  //    The loading lane fetches the global chunk that belongs at its LDS position.
+  //  * The fused tile K_f of the distr path is written by the waves themselves: rows padded by
+  //    8 elements (16-byte aligned, consecutive rows 4 banks apart).
+  //  * The raw K tile of the distr path is only read by 2-byte gathers down a column: an odd
+  //    number of dwords per row keeps the 64 rows of a wave on distinct banks.
+  static constexpr int ROWB = D * 2;              // bytes of an unpadded row
+  static constexpr int TILEB = kBc * ROWB;        // bytes of an unpadded 64-row tile
+  static constexpr int KXS = KRED + 8;            // K_f row stride in elements (distr)
+  static constexpr int KX_BYTES = DISTR ? kBc * KXS * 2 : TILEB;   // one Kx buffer
+  static constexpr int KRS = D + 2;               // raw K tile row stride in elements (distr only)
   static constexpr int SP = KRED / NW;            // fused slots each wave builds per key row
   static constexpr int NGATHER = SP * G;          // 2-byte gathers per lane per tile (= D / NW)
   static constexpr int KSTEPS = KRED / 16;        // MFMA steps of the score product
 };
+
+// Tuning switches (compile-time; the defaults are what the library ships with).
+#ifndef DA_HINTS
+#define DA_HINTS 1          // 1: interleave MFMA / LDS / vector instructions with scheduling groups
+#endif
+#ifndef DA_KPF
+#define DA_KPF 4            // LDS operand reads issued ahead of the first MFMA of a phase
+#endif
+#ifndef DA_WAVES_PER_EU
+#define DA_WAVES_PER_EU 2   // occupancy target (waves per SIMD) given to the register allocator
+#endif
 
 // Rows whose running maximum moved by less than this (in log2 units) keep their old reference
 // maximum: P is then at most 2^kTau, the sums stay exact ratios, and the accumulator rescale
@@ -101,18 +124,21 @@ struct Cfg {
 constexpr float kTau = 8.0f;
 
 template <int D, int BR, int KRED, bool DISTR>
-__global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
+__global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     bf16* __restrict__ o, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Tq,
     int causal, float scale_log2e, int total_units) {
   using C = Cfg<D, BR, KRED, DISTR>;
-  using kx_t = typename std::conditional<DISTR, f16, bf16>::type;
   using kx8 = typename std::conditional<DISTR, f16x8, bf16x8>::type;
-  constexpr int KX_BUF = kBc * C::KXS;   // elements per Kx buffer
-  constexpr int V_BUF = kBc * C::VS;
   // Kx and V tiles are double-buffered: while tile i multiplies, tile i+1 (V) / i+2 (K) lands.
-  __shared__ __attribute__((aligned(16))) kx_t kx_lds[2 * KX_BUF];
-  __shared__ __attribute__((aligned(16))) bf16 v_lds[2 * V_BUF];
+  // Each buffer is a separate LDS object: the compiler can then tell that the operand reads of
+  // one buffer do not depend on the direct loads still in flight into the other.
+  __shared__ __attribute__((aligned(1024))) char kx_lds0[C::KX_BYTES];
+  __shared__ __attribute__((aligned(1024))) char kx_lds1[C::KX_BYTES];
+  __shared__ __attribute__((aligned(1024))) char v_lds0[C::TILEB];
+  __shared__ __attribute__((aligned(1024))) char v_lds1[C::TILEB];
+  auto kx_buf = [&](int par) -> char* { return par ? kx_lds1 : kx_lds0; };
+  auto v_buf = [&](int par) -> char* { return par ? v_lds1 : v_lds0; };
   __shared__ __attribute__((aligned(16))) bf16 kraw_lds[DISTR ? kBc * C::KRS : 8];
   __shared__ uint8_t perm_lds[DISTR ? D : 4];
 
@@ -191,34 +217,51 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
   // K and V rows are fetched through buffer descriptors: the per-lane byte offset inside a
   // tile is fixed, the tile advances through the scalar offset, and rows past the end of the
   // head read as zero (hardware range check), so a tile costs no address arithmetic.
-  u32x4 kst[C::CPT], vst[C::CPT];
   const unsigned head_bytes = (unsigned)N * D * 2;
   const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kh, 0, head_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)vh, 0, head_bytes, 0x00020000);
-  const int st_voff = ((tid / C::CH) * D + (tid % C::CH) * 8) * 2;   // chunk j adds j * (T / CH) rows
-  auto load_rows = [&](__amdgpu_buffer_rsrc_t rsrc, int tile, u32x4 (&st)[C::CPT]) {
-    const int soff = tile * (kBc * D * 2);
+
+  // Direct global->LDS tile loads. Wave-level load j of this wave fills the 1 KB block
+  // j*NW + wave of the tile; lane i owns the 16 bytes at offset 16*i of that block, i.e. LDS
+  // row (slot / CH), chunk position (slot % CH) with slot = 64*block + i, and fetches the global
+  // chunk the swizzle assigns to that position.
+  int dma_k[DISTR ? 1 : C::CPT], dma_v[C::CPT];
+#pragma unroll
+  for (int j = 0; j < C::CPT; ++j) {
+    const int slot = (j * C::NW + wave) * 64 + lane;
+    const int row = slot / C::CH, pc = slot % C::CH;
+    if constexpr (!DISTR) dma_k[j] = row * C::ROWB + (pc ^ (D == 128 ? (row & 15) : ((row >> 1) & 7))) * 16;
+    const int lseg = (pc >> 1) ^ (D == 128 ? (row & 7) : ((row >> 1) & 3));
+    dma_v[j] = row * C::ROWB + (lseg * 2 + (pc & 1)) * 16;
+  }
+  typedef __attribute__((address_space(3))) void lds_void;
+  auto dma_tile = [&](__amdgpu_buffer_rsrc_t rsrc, int tile, const int* voff, char* dst) {
+    const int soff = tile * C::TILEB;
 #pragma unroll
     for (int j = 0; j < C::CPT; ++j)
-      st[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, st_voff + j * (C::T / C::CH) * D * 2, soff, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(dst + (j * C::NW + wave) * 1024), 16,
+                                               voff[j], soff, 0, 0);
   };
-  auto store_v = [&](int buf) {
+  auto dma_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+
+  // distr: the raw K tile goes through registers into the gather layout
+  u32x4 kst[DISTR ? C::CPT : 1];
+  const int st_voff = ((tid / C::CH) * D + (tid % C::CH) * 8) * 2;   // chunk j adds j * (T / CH) rows
+  auto load_kraw = [&](int tile) {
+    if constexpr (DISTR) {
+      const int soff = tile * C::TILEB;
 #pragma unroll
-    for (int j = 0; j < C::CPT; ++j) {
-      int id = tid + j * C::T;
-      *(u32x4*)(v_lds + buf * V_BUF + (id / C::CH) * C::VS + (id % C::CH) * 8) = vst[j];
+      for (int j = 0; j < C::CPT; ++j)
+        kst[j] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, st_voff + j * (C::T / C::CH) * C::ROWB, soff, 0);
     }
   };
-  auto store_k = [&](int buf) {   // exact: K tile as it is; distr: raw tile for the gathers
+  auto store_kraw = [&]() {
+    if constexpr (DISTR) {
 #pragma unroll
-    for (int j = 0; j < C::CPT; ++j) {
-      int id = tid + j * C::T;
-      int row = id / C::CH, col = (id % C::CH) * 8;
-      if constexpr (DISTR) {
-        unsigned* dst = (unsigned*)(kraw_lds + row * C::KRS + col);
+      for (int j = 0; j < C::CPT; ++j) {
+        int id = tid + j * C::T;
+        unsigned* dst = (unsigned*)(kraw_lds + (id / C::CH) * C::KRS + (id % C::CH) * 8);
         dst[0] = kst[j][0]; dst[1] = kst[j][1]; dst[2] = kst[j][2]; dst[3] = kst[j][3];
-      } else {
-        *(u32x4*)(kx_lds + buf * KX_BUF + row * C::KXS + col) = kst[j];
       }
     }
   };
@@ -245,7 +288,7 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
           fused[sl] = to_half_sat(acc);
         }
       }
-      f16* dst = (f16*)kx_lds + buf * KX_BUF + lane * C::KXS + wave * C::SP;
+      f16* dst = (f16*)kx_buf(buf) + lane * C::KXS + wave * C::SP;
       if constexpr (C::SP % 8 == 0) {
 #pragma unroll
         for (int c8 = 0; c8 < C::SP / 8; ++c8) {
@@ -271,21 +314,41 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
   float m_ref = -INFINITY;   // reference row max, log2 units (scaled); at most kTau below the true max
   float l_run = 0.0f;        // row sum over this lane's half of the keys, relative to m_ref
 
-  // LDS addresses of this lane's operands inside buffer 0
-  const kx_t* ka_base = kx_lds + lq * C::KXS + 8 * hh;
-  const bf16* vt_base = v_lds + (((lane & 15) >> 2) + 4 * hh) * C::VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  // LDS byte offsets of this lane's operands inside a buffer.
+  // Score product, A operand: row lq (+32 per key block), logical chunk 2*s + hh.
+  int ka_off[C::KSTEPS];
+#pragma unroll
+  for (int s = 0; s < C::KSTEPS; ++s) {
+    if constexpr (DISTR) ka_off[s] = (lq * C::KXS + 16 * s + 8 * hh) * 2;
+    else ka_off[s] = lq * C::ROWB + ((2 * s + hh) ^ (D == 128 ? (lq & 15) : ((lq >> 1) & 7))) * 16;
+  }
+  // P.V, A operand via transposing reads: lane addresses row 4*hh + (lane%16)/4 (+8, +16*tt),
+  // logical 32-byte segment 2*mb + (lane/16)%2, 8-byte piece lane%4 of it.
+  int va_off[D / 32];
+  {
+    const int row_l = 4 * hh + ((lane & 15) >> 2);
+    const int swz = D == 128 ? (row_l & 7) : ((row_l >> 1) & 3);
+#pragma unroll
+    for (int mb = 0; mb < D / 32; ++mb)
+      va_off[mb] = row_l * C::ROWB + ((2 * mb + ((lane >> 4) & 1)) ^ swz) * 32 + 8 * (lane & 3);
+  }
 
   // S^T = Kx . Qx^T for the Kx tile in buffer `buf`: register i of block mb holds key
   // 32*mb + 8*(i/4) + 4*hh + i%4 of the tile.
   auto qk = [&](int buf, f32x16 (&sacc)[2]) {
-    const kx_t* base = ka_base + buf * KX_BUF;
+    const char* base = kx_buf(buf);
+    constexpr int MB_STEP = 32 * (DISTR ? C::KXS * 2 : C::ROWB);
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[mb][i] = 0.0f;
 #pragma unroll
       for (int s = 0; s < C::KSTEPS; ++s) {
-        kx8 a = *(const kx8*)(base + mb * 32 * C::KXS + 16 * s);
+#ifdef DA_ABL_NOKREAD
+        kx8 a = qop[(s + 1) % C::KSTEPS];
+#else
+        kx8 a = *(const kx8*)(base + ka_off[s] + mb * MB_STEP);
+#endif
         sacc[mb] = mfma_32x32x16(a, qop[s], sacc[mb]);
       }
     }
@@ -334,9 +397,12 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
   // instead of emitting them one after the other.
   auto body = [&](auto mask_next_c, auto next_c, int it, int par, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
     constexpr bool HAS_NEXT = decltype(next_c)::value;
+    // The buffers these loads fill were last read in the previous iteration, which every wave
+    // has left (barrier): K(it+2) replaces K(it), V(it+1) replaces V(it-1).
     if constexpr (HAS_NEXT) {
-      load_rows(k_rsrc, it + 2, kst);
-      load_rows(v_rsrc, it + 1, vst);
+      if constexpr (DISTR) load_kraw(it + 2);
+      else dma_tile(k_rsrc, it + 2, dma_k, kx_buf(par));
+      dma_tile(v_rsrc, it + 1, dma_v, v_buf(par ^ 1));
     }
     if constexpr (HAS_NEXT) qk(par ^ 1, sn);
     // The row sum is taken over the bf16-rounded P, the values P.V really uses (one bf16 dot
@@ -350,8 +416,13 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
+#ifdef DA_ABL_NOEXP
+          float p0 = __builtin_fmaf(sc[mb][i], scale_log2e, -m_ref);
+          float p1 = __builtin_fmaf(sc[mb][i + 1], scale_log2e, -m_ref);
+#else
           float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mb][i], scale_log2e, -m_ref));
           float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mb][i + 1], scale_log2e, -m_ref));
+#endif
           bf16x2 pr = {(bf16)p0, (bf16)p1};
           pop[mb * 2 + (i >> 3)][i & 7] = pr[0];
           pop[mb * 2 + (i >> 3)][(i & 7) + 1] = pr[1];
@@ -362,13 +433,18 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
     }
     // ---- O^T += V^T . P^T: step tt covers keys 16*tt + {8*(j/4) + 4*hh + j%4} of the tile,
     // i.e. V rows 16*tt + 4*hh + 0..3 and 16*tt + 8 + 4*hh + 0..3.
-    const bf16* vb = vt_base + par * V_BUF;
+    const char* vb = v_buf(par);
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt) {
 #pragma unroll
       for (int mb = 0; mb < D / 32; ++mb) {
-        const bf16* p0 = vb + (16 * tt) * C::VS + 32 * mb;
-        bf16x8 a = lds_read_tr_pair(p0, p0 + 8 * C::VS);
+        const char* p0 = vb + va_off[mb] + 16 * tt * C::ROWB;
+#ifdef DA_ABL_NOVREAD
+        bf16x8 a = pop[(tt + mb + 1) & 3];
+        (void)p0;
+#else
+        bf16x8 a = lds_read_tr_pair((const bf16*)p0, (const bf16*)(p0 + 8 * C::ROWB));
+#endif
         oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pop[tt], oacc[mb], 0, 0, 0);
       }
     }
@@ -377,19 +453,21 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
     // ---- scheduling hints (groups are filled in this order) -----------------------------------
     // One MFMA occupies the issue port for 8 cycles and the matrix pipe for 32: up to 6 vector
     // instructions fit beside it. Operands are fetched from LDS four MFMAs ahead.
+#if DA_HINTS
     {
       constexpr int N_QK = HAS_NEXT ? 2 * C::KSTEPS : 0;
       constexpr int N_PV = D / 8;
       constexpr int VALU_PER_MFMA = (150 + N_QK + N_PV - 1) / (N_QK + N_PV);
-      __builtin_amdgcn_sched_group_barrier(0x100, HAS_NEXT ? 4 : 8, 0);
+      constexpr int PF = DA_KPF < N_QK ? DA_KPF : N_QK;
+      __builtin_amdgcn_sched_group_barrier(0x100, HAS_NEXT ? PF : 2 * DA_KPF, 0);
 #pragma unroll
-      for (int i = 0; i < N_QK - 4; ++i) {
+      for (int i = 0; i < N_QK - PF; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one score MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        // a K operand, four MFMAs ahead
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        // a K operand, PF MFMAs ahead
         __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER_MFMA, 0);
       }
 #pragma unroll
-      for (int i = 0; i < (N_QK < 4 ? N_QK : 4); ++i) {
+      for (int i = 0; i < PF; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one score MFMA
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);        // K operands are all in: first V operands
         __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER_MFMA, 0);
@@ -401,37 +479,40 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
         __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER_MFMA, 0);
       }
     }
+#endif
     if constexpr (HAS_NEXT) {
       move_reference(mt_next);
-      // ---- land the prefetched tiles: V(it+1) and K(it+2) (buffers whose readers are done) ----
-      store_v(par ^ 1);
-      store_k(par);
-      if constexpr (DISTR) {
+      if constexpr (DISTR) {   // raw K(it+2) -> gather layout -> fused tile K_f(it+2)
+        store_kraw();
         __syncthreads();
         fuse(par);
       }
+      dma_wait();              // this wave's direct loads have landed
     }
+#ifndef DA_ABL_NOBARRIER
     __syncthreads();
+#endif
   };
 
   // ---- prologue: tiles 0 (K, V) and 1 (K) into LDS, scores of tile 0 ---------------------------
-  load_rows(k_rsrc, 0, kst);
-  load_rows(v_rsrc, 0, vst);
-  store_k(0);
-  store_v(0);
+  dma_tile(v_rsrc, 0, dma_v, v_lds0);
   if constexpr (DISTR) {
+    load_kraw(0);
+    store_kraw();
     __syncthreads();
     fuse(0);
-    __syncthreads();
-  }
-  if (n_tiles > 1) {
-    load_rows(k_rsrc, 1, kst);
-    store_k(1);
-    if constexpr (DISTR) {
+    if (n_tiles > 1) {
+      load_kraw(1);
+      __syncthreads();   // every wave is done gathering tile 0
+      store_kraw();
       __syncthreads();
       fuse(1);
     }
+  } else {
+    dma_tile(k_rsrc, 0, dma_k, kx_lds0);
+    if (n_tiles > 1) dma_tile(k_rsrc, 1, dma_k, kx_lds1);
   }
+  dma_wait();
   __syncthreads();
 
   const std::true_type yes;
