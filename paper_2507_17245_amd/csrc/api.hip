@@ -81,34 +81,47 @@ size_t perm_bytes(const Resolved& r) {
   return (n + 255) & ~(size_t)255;
 }
 
-// Device buffer for the permutation table: caller's perm_out, caller's workspace, or ours.
-int get_perm_buffer(const da_params* p, const Resolved& r, uint8_t** out) {
-  if (p->perm_out) { *out = p->perm_out; return DA_OK; }
-  const size_t need = perm_bytes(r);
+// Transposed half-precision copy of K that the bf16 distr path reads: [B][Hkv][d][Npad].
+size_t kt_bytes(const Resolved& r) {
+  if (r.dtype != DA_BF16) return 0;
+  size_t npad = (size_t)((r.pb.N + da::kBc - 1) / da::kBc) * da::kBc;
+  size_t n = (size_t)r.pb.B * r.pb.Hkv * r.pb.d * npad * 2;
+  return (n + 255) & ~(size_t)255;
+}
+
+// Device scratch of the distr path: [K^T copy | permutation table], from the caller's workspace
+// or from the library-owned one. The table goes to perm_out instead when the caller gave one.
+int get_scratch(const da_params* p, const Resolved& r, bool need_perm, uint8_t** perm, void** kt) {
+  const size_t kt_need = kt_bytes(r);
+  const size_t need = kt_need + perm_bytes(r);
+  char* base = nullptr;
   if (p->workspace) {
     if (p->workspace_bytes < need)
       return fail(DA_ERR_WORKSPACE, "workspace of %zu bytes, %zu needed", p->workspace_bytes, need);
-    *out = (uint8_t*)p->workspace;
-    return DA_OK;
-  }
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(DA_ERR_HIP, "hipGetDevice failed");
-  std::lock_guard<std::mutex> lock(g_ws_mutex);
-  if (g_ws_bytes[dev] < need) {
-    if (g_ws_ptr[dev]) {
-      // the old buffer may still be read by enqueued work
-      if (hipDeviceSynchronize() != hipSuccess) return fail(DA_ERR_HIP, "hipDeviceSynchronize failed");
-      (void)hipFree(g_ws_ptr[dev]);
-      g_ws_ptr[dev] = nullptr;
-      g_ws_bytes[dev] = 0;
+    if (((uintptr_t)p->workspace & 255u) != 0) return fail(DA_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    base = (char*)p->workspace;
+  } else {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(DA_ERR_HIP, "hipGetDevice failed");
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (g_ws_bytes[dev] < need) {
+      if (g_ws_ptr[dev]) {
+        // the old buffer may still be read by enqueued work
+        if (hipDeviceSynchronize() != hipSuccess) return fail(DA_ERR_HIP, "hipDeviceSynchronize failed");
+        (void)hipFree(g_ws_ptr[dev]);
+        g_ws_ptr[dev] = nullptr;
+        g_ws_bytes[dev] = 0;
+      }
+      void* ptr = nullptr;
+      hipError_t e = hipMalloc(&ptr, need);
+      if (e != hipSuccess) return fail(DA_ERR_WORKSPACE, "hipMalloc(%zu) failed: %s", need, hipGetErrorString(e));
+      g_ws_ptr[dev] = ptr;
+      g_ws_bytes[dev] = need;
     }
-    void* ptr = nullptr;
-    hipError_t e = hipMalloc(&ptr, need);
-    if (e != hipSuccess) return fail(DA_ERR_WORKSPACE, "hipMalloc(%zu) failed: %s", need, hipGetErrorString(e));
-    g_ws_ptr[dev] = ptr;
-    g_ws_bytes[dev] = need;
+    base = (char*)g_ws_ptr[dev];
   }
-  *out = (uint8_t*)g_ws_ptr[dev];
+  *kt = kt_need ? (void*)base : nullptr;
+  *perm = (need_perm && p->perm_out) ? p->perm_out : (uint8_t*)(base + kt_need);
   return DA_OK;
 }
 
@@ -124,21 +137,28 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
   rc = check_tensors(q, k, v, o);
   if (rc) return rc;
   if (r.dtype == DA_BF16 && !da::attn_bf16_supported(r.pb, distr ? 1 : 0))
-    return fail(DA_ERR_UNSUPPORTED, "bf16 kernels need n_groups in {16, 32, 64, 128} (a multiple of the MFMA step) "
-                "and at least 4 groups per wavefront; got d=%d Br=%d n_groups=%d", p->d, p->Br, p->n_groups);
+    return fail(DA_ERR_UNSUPPORTED, "bf16 kernels need n_groups in {16, 32, 64, 128} (a multiple of the MFMA step); "
+                "got d=%d Br=%d n_groups=%d", p->d, p->Br, p->n_groups);
   const uint8_t* perm = nullptr;
-  if (distr && p->perm_in) {
-    perm = p->perm_in;
-  } else if (distr) {
+  void* kt = nullptr;
+  if (distr) {
     uint8_t* table = nullptr;
-    rc = get_perm_buffer(p, r, &table);
+    rc = get_scratch(p, r, p->perm_in == nullptr, &table, &kt);
     if (rc) return rc;
-    rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, table, p->hash_out, r.stream), "lsh_group launch");
-    if (rc) return rc;
-    perm = table;
+    if (p->perm_in) {
+      perm = p->perm_in;
+    } else {
+      rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, table, p->hash_out, r.stream), "lsh_group launch");
+      if (rc) return rc;
+      perm = table;
+    }
+    if (r.dtype == DA_BF16) {
+      rc = check_launch(da::launch_kt_prepass(k, kt, r.pb, r.stream), "key pre-pass launch");
+      if (rc) return rc;
+    }
   }
   hipError_t e = (r.dtype == DA_BF16)
-                     ? da::launch_attn_bf16(q, k, v, o, perm, r.pb, distr ? 1 : 0, r.stream)
+                     ? da::launch_attn_bf16(q, k, v, o, perm, kt, r.pb, distr ? 1 : 0, r.stream)
                      : da::launch_attn_f32(q, k, v, o, perm, r.pb, distr ? 1 : 0, r.stream);
   return check_launch(e, "attention launch");
 }
@@ -187,7 +207,7 @@ int distr_attn_lsh_group(const void* q, const da_params* p) {
 size_t distr_attn_workspace_bytes(const da_params* p) {
   Resolved r;
   if (resolve(p, true, &r)) return 0;
-  return perm_bytes(r);
+  return kt_bytes(r) + perm_bytes(r);
 }
 
 int distr_attn_hyperplanes(uint64_t seed, int n_planes, int Br, float* host_out) {

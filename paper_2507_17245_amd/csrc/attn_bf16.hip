@@ -43,13 +43,14 @@ __device__ inline f32x16 mfma_32x32x16(f16x8 a, f16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
-__device__ inline bf16x8 lds_read_tr_pair(const bf16* p0, const bf16* p1) {
-  // Two transposing LDS reads (ds_read_b64_tr_b16): within each group of 16 lanes, lane i
-  // receives element (i % 4) of the 8-byte chunks addressed by lanes 4j + i/4, j = 0..3.
+// Two transposing LDS reads (ds_read_b64_tr_b16): within each group of 16 lanes, lane i
+// receives element (i % 4) of the 8-byte chunks addressed by lanes 4j + i/4, j = 0..3.
+template <typename V8>
+__device__ inline V8 lds_read_tr_pair(const void* p0, const void* p1) {
   s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p0);
   s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p1);
   s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-  return __builtin_bit_cast(bf16x8, r);
+  return __builtin_bit_cast(V8, r);
 }
 
 // Exchange between the wave halves: v_permlane32_swap swaps the upper 32 lanes of its first
@@ -93,23 +94,23 @@ struct Cfg {
   //          32-byte segment' = segment ^ (row & 7)         (D = 128)
   //          32-byte segment' = segment ^ ((row >> 1) & 3)  (D = 64)
   //    The loading lane fetches the global chunk that belongs at its LDS position.
-  //  * The fused tile K_f of the distr path is written by the waves themselves: rows padded by
-  //    8 elements (16-byte aligned, consecutive rows 4 banks apart).
-  //  * The raw K tile of the distr path is only read by 2-byte gathers down a column: an odd
-  //    number of dwords per row keeps the 64 rows of a wave on distinct banks.
-  static constexpr int ROWB = D * 2;              // bytes of an unpadded row
+  //  * distr path: the keys arrive transposed and in half precision (K^T, one row of 64 keys =
+  //    128 bytes per channel, written once per forward by the key pre-pass). The raw tile is
+  //    loaded unswizzled; the fused tile K_f^T (one 128-byte row per group) is written by the
+  //    waves and read back with transposing accesses, so it uses the V swizzle for 128-byte rows.
+  static constexpr int ROWB = D * 2;              // bytes of an unpadded K / V row
   static constexpr int TILEB = kBc * ROWB;        // bytes of an unpadded 64-row tile
-  static constexpr int KXS = KRED + 8;            // K_f row stride in elements (distr)
-  static constexpr int KX_BYTES = DISTR ? kBc * KXS * 2 : TILEB;   // one Kx buffer
-  static constexpr int KRS = D + 2;               // raw K tile row stride in elements (distr only)
-  static constexpr int SP = KRED / NW;            // fused slots each wave builds per key row
-  static constexpr int NGATHER = SP * G;          // 2-byte gathers per lane per tile (= D / NW)
+  static constexpr int KTROWB = kBc * 2;          // bytes of a K^T / K_f^T row (64 keys)
+  static constexpr int KX_BYTES = DISTR ? KRED * KTROWB : TILEB;   // one Kx buffer: K_f^T or K
+  static constexpr int KT_BYTES = D * KTROWB;     // raw K^T tile (distr)
+  static constexpr int KT_LOADS = D / 8 / NW;     // 1 KB direct loads per wave for a K^T tile
+  static constexpr int FUSE_OUT = (KRED * 8 + T - 1) / T;   // 16-byte fused outputs per thread and tile
   static constexpr int KSTEPS = KRED / 16;        // MFMA steps of the score product
 };
 
 // Tuning switches (compile-time; the defaults are what the library ships with).
 #ifndef DA_HINTS
-#define DA_HINTS 1          // 1: interleave MFMA / LDS / vector instructions with scheduling groups
+#define DA_HINTS 0          // 1: force an MFMA / LDS / vector interleave with scheduling groups (measured: no gain)
 #endif
 #ifndef DA_KPF
 #define DA_KPF 4            // LDS operand reads issued ahead of the first MFMA of a phase
@@ -126,8 +127,8 @@ constexpr float kTau = 8.0f;
 template <int D, int BR, int KRED, bool DISTR>
 __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-    bf16* __restrict__ o, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Tq,
-    int causal, float scale_log2e, int total_units) {
+    bf16* __restrict__ o, const uint8_t* __restrict__ perm, const f16* __restrict__ kt, int Npad,
+    int H, int Hkv, int N, int Tq, int causal, float scale_log2e, int total_units) {
   using C = Cfg<D, BR, KRED, DISTR>;
   using kx8 = typename std::conditional<DISTR, f16x8, bf16x8>::type;
   // Kx and V tiles are double-buffered: while tile i multiplies, tile i+1 (V) / i+2 (K) lands.
@@ -139,8 +140,13 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   __shared__ __attribute__((aligned(1024))) char v_lds1[C::TILEB];
   auto kx_buf = [&](int par) -> char* { return par ? kx_lds1 : kx_lds0; };
   auto v_buf = [&](int par) -> char* { return par ? v_lds1 : v_lds0; };
-  __shared__ __attribute__((aligned(16))) bf16 kraw_lds[DISTR ? kBc * C::KRS : 8];
-  __shared__ uint8_t perm_lds[DISTR ? D : 4];
+  __shared__ __attribute__((aligned(1024))) char kt_lds0[DISTR ? C::KT_BYTES : 16];   // raw K^T tiles
+  __shared__ __attribute__((aligned(1024))) char kt_lds1[DISTR ? C::KT_BYTES : 16];
+  auto kt_buf = [&](int par) -> char* { return par ? kt_lds1 : kt_lds0; };
+  // The block's permutation is only needed while the prologue builds the sampled-query operands
+  // and the fusion offsets: it borrows the head of the second V buffer, which receives its
+  // first tile in the first loop iteration (after the prologue's barriers).
+  uint8_t* perm_lds = (uint8_t*)v_lds1;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -199,13 +205,21 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
 #pragma unroll
   for (int s = 0; s < C::KSTEPS; ++s) asm volatile("" : "+v"(qop[s]));
 
-  // ---- fusion gather offsets (bytes into kraw_lds), fixed for the Q block -------------------
-  // Thread (row n = lane, part = wave) builds K_f[n][part*SP .. part*SP+SP-1].
-  int goff[DISTR ? C::NGATHER : 1];
+  // ---- fusion bookkeeping, fixed for the Q block ------------------------------------------------
+  // Fused output u of this thread is the 16-byte piece (8 keys) number idx % 8 of group
+  // idx / 8, idx = tid + u*T: it sums the same piece of the group's G channel rows of the raw
+  // K^T tile and lands in row idx / 8 of K_f^T at the swizzled position.
+  int f_src[DISTR ? C::FUSE_OUT : 1][DISTR ? C::G : 1];
+  int f_dst[DISTR ? C::FUSE_OUT : 1];
   if constexpr (DISTR) {
 #pragma unroll
-    for (int i = 0; i < C::NGATHER; ++i)
-      goff[i] = (lane * C::KRS + perm_lds[wave * C::NGATHER + i]) * 2;
+    for (int u = 0; u < C::FUSE_OUT; ++u) {
+      const int idx = min(tid + u * C::T, KRED * 8 - 1);
+      const int j = idx >> 3, c8 = idx & 7;
+#pragma unroll
+      for (int g = 0; g < C::G; ++g) f_src[u][g] = perm_lds[j * C::G + g] * C::KTROWB + c8 * 16;
+      f_dst[u] = j * C::KTROWB + ((((c8 >> 1) ^ ((j >> 1) & 3)) << 1) | (c8 & 1)) * 16;
+    }
   }
 
   const int n_end = causal ? min(N, r0 + BR) : N;
@@ -235,72 +249,46 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
     dma_v[j] = row * C::ROWB + (lseg * 2 + (pc & 1)) * 16;
   }
   typedef __attribute__((address_space(3))) void lds_void;
-  auto dma_tile = [&](__amdgpu_buffer_rsrc_t rsrc, int tile, const int* voff, char* dst) {
-    const int soff = tile * C::TILEB;
+  auto dma_blocks = [&](auto n_c, __amdgpu_buffer_rsrc_t rsrc, int soff, const int* voff, char* dst) {
 #pragma unroll
-    for (int j = 0; j < C::CPT; ++j)
+    for (int j = 0; j < decltype(n_c)::value; ++j)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(dst + (j * C::NW + wave) * 1024), 16,
                                                voff[j], soff, 0, 0);
   };
+  auto dma_tile = [&](__amdgpu_buffer_rsrc_t rsrc, int tile, const int* voff, char* dst) {
+    dma_blocks(std::integral_constant<int, C::CPT>(), rsrc, tile * C::TILEB, voff, dst);
+  };
   auto dma_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
-  // distr: the raw K tile goes through registers into the gather layout
-  u32x4 kst[DISTR ? C::CPT : 1];
-  const int st_voff = ((tid / C::CH) * D + (tid % C::CH) * 8) * 2;   // chunk j adds j * (T / CH) rows
-  auto load_kraw = [&](int tile) {
-    if constexpr (DISTR) {
-      const int soff = tile * C::TILEB;
+  // distr: raw K^T tile (D channel rows of 64 keys) by direct loads, unswizzled: LDS row =
+  // channel, so 1 KB block number (j*NW + wave) holds 8 channel rows.
+  const __amdgpu_buffer_rsrc_t kt_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(DISTR ? kt + (size_t)(b * Hkv + hk) * D * Npad : nullptr), 0, (unsigned)D * Npad * 2, 0x00020000);
+  int dma_kt[DISTR ? C::KT_LOADS : 1];
+  if constexpr (DISTR) {
 #pragma unroll
-      for (int j = 0; j < C::CPT; ++j)
-        kst[j] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, st_voff + j * (C::T / C::CH) * C::ROWB, soff, 0);
+    for (int j = 0; j < C::KT_LOADS; ++j) {
+      const int slot = (j * C::NW + wave) * 64 + lane;
+      dma_kt[j] = (slot >> 3) * Npad * 2 + (slot & 7) * 16;
     }
+  }
+  auto dma_kt_tile = [&](int tile, int buf) {
+    if constexpr (DISTR)
+      dma_blocks(std::integral_constant<int, C::KT_LOADS>(), kt_rsrc, tile * C::KTROWB, dma_kt, kt_buf(buf));
   };
-  auto store_kraw = [&]() {
+  // ---- fusion (Sec. 3.2): K_f^T[j][n] = sum over the group's channels c of K^T[c][n], eight keys
+  // at a time with packed half adds. For G* = 2 the sum of two bf16-valued halves is rounded to
+  // half once; larger groups add pairwise.
+  auto fuse = [&](int buf) {   // raw tile in kt_buf(buf) -> K_f^T in kx_buf(buf)
     if constexpr (DISTR) {
+      char* dst = kx_buf(buf);
+      const char* src = kt_buf(buf);
 #pragma unroll
-      for (int j = 0; j < C::CPT; ++j) {
-        int id = tid + j * C::T;
-        unsigned* dst = (unsigned*)(kraw_lds + (id / C::CH) * C::KRS + (id % C::CH) * 8);
-        dst[0] = kst[j][0]; dst[1] = kst[j][1]; dst[2] = kst[j][2]; dst[3] = kst[j][3];
-      }
-    }
-  };
-  // ---- fusion (Sec. 3.2): K_f[n][j] = sum of the group's key channels, in float, rounded to
-  // half once. Two members are gathered into one register and summed by a bf16 dot product
-  // with (1, 1).
-  auto fuse = [&](int buf) {
-    if constexpr (DISTR) {
-      const char* kraw = (const char*)kraw_lds;
-      const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
-      f16 fused[C::SP];
+      for (int u = 0; u < C::FUSE_OUT; ++u) {
+        f16x8 acc = *(const f16x8*)(src + f_src[u][0]);
 #pragma unroll
-      for (int sl = 0; sl < C::SP; ++sl) {
-        if constexpr (C::G == 1) {
-          fused[sl] = to_half_sat((float)*(const bf16*)(kraw + goff[sl]));
-        } else {
-          float acc = 0.0f;
-#pragma unroll
-          for (int g = 0; g < C::G; g += 2) {
-            bf16x2 pr = {*(const bf16*)(kraw + goff[sl * C::G + g]),
-                         *(const bf16*)(kraw + goff[sl * C::G + g + 1])};
-            acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
-          }
-          fused[sl] = to_half_sat(acc);
-        }
-      }
-      f16* dst = (f16*)kx_buf(buf) + lane * C::KXS + wave * C::SP;
-      if constexpr (C::SP % 8 == 0) {
-#pragma unroll
-        for (int c8 = 0; c8 < C::SP / 8; ++c8) {
-          f16x8 pk;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) pk[j] = fused[c8 * 8 + j];
-          *(f16x8*)(dst + c8 * 8) = pk;
-        }
-      } else {
-        static_assert(!DISTR || C::SP % 8 == 0 || C::SP == 4, "fused slots per wave: 4 or a multiple of 8");
-        f16x4 pk = {fused[0], fused[1], fused[2], fused[3]};
-        *(f16x4*)dst = pk;
+        for (int g = 1; g < C::G; ++g) acc += *(const f16x8*)(src + f_src[u][g]);
+        if (KRED * 8 % C::T == 0 || tid + u * C::T < KRED * 8) *(f16x8*)(dst + f_dst[u]) = acc;
       }
     }
   };
@@ -315,12 +303,22 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   float l_run = 0.0f;        // row sum over this lane's half of the keys, relative to m_ref
 
   // LDS byte offsets of this lane's operands inside a buffer.
-  // Score product, A operand: row lq (+32 per key block), logical chunk 2*s + hh.
-  int ka_off[C::KSTEPS];
+  // Score product, A operand (exact): row lq (+32 per key block), logical chunk 2*s + hh.
+  int ka_off[DISTR ? 4 : C::KSTEPS];
+  if constexpr (DISTR) {
+    // K_f^T is read like V: lane addresses group row 8*hh + 4*half + (lane%16)/4 (+16*s), 32-byte
+    // segment 2*mb + (lane/16)%2 (keys 32*mb + 16*((lane/16)%2) ..), 8-byte piece lane%4.
+    const int r4 = (lane & 15) >> 2;
 #pragma unroll
-  for (int s = 0; s < C::KSTEPS; ++s) {
-    if constexpr (DISTR) ka_off[s] = (lq * C::KXS + 16 * s + 8 * hh) * 2;
-    else ka_off[s] = lq * C::ROWB + ((2 * s + hh) ^ (D == 128 ? (lq & 15) : ((lq >> 1) & 7))) * 16;
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+        ka_off[mb * 2 + hf] = (8 * hh + 4 * hf + r4) * C::KTROWB +
+                              ((2 * mb + ((lane >> 4) & 1)) ^ ((2 * hf + (r4 >> 1)) & 3)) * 32 + 8 * (lane & 3);
+  } else {
+#pragma unroll
+    for (int s = 0; s < C::KSTEPS; ++s)
+      ka_off[s] = lq * C::ROWB + ((2 * s + hh) ^ (D == 128 ? (lq & 15) : ((lq >> 1) & 7))) * 16;
   }
   // P.V, A operand via transposing reads: lane addresses row 4*hh + (lane%16)/4 (+8, +16*tt),
   // logical 32-byte segment 2*mb + (lane/16)%2, 8-byte piece lane%4 of it.
@@ -337,17 +335,21 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   // 32*mb + 8*(i/4) + 4*hh + i%4 of the tile.
   auto qk = [&](int buf, f32x16 (&sacc)[2]) {
     const char* base = kx_buf(buf);
-    constexpr int MB_STEP = 32 * (DISTR ? C::KXS * 2 : C::ROWB);
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[mb][i] = 0.0f;
 #pragma unroll
       for (int s = 0; s < C::KSTEPS; ++s) {
+        kx8 a;
 #ifdef DA_ABL_NOKREAD
-        kx8 a = qop[(s + 1) % C::KSTEPS];
+        a = qop[(s + 1) % C::KSTEPS];
 #else
-        kx8 a = *(const kx8*)(base + ka_off[s] + mb * MB_STEP);
+        if constexpr (DISTR)
+          a = lds_read_tr_pair<kx8>(base + ka_off[mb * 2] + s * 16 * C::KTROWB,
+                                    base + ka_off[mb * 2 + 1] + s * 16 * C::KTROWB);
+        else
+          a = *(const kx8*)(base + ka_off[s] + mb * 32 * C::ROWB);
 #endif
         sacc[mb] = mfma_32x32x16(a, qop[s], sacc[mb]);
       }
@@ -400,8 +402,16 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
     // The buffers these loads fill were last read in the previous iteration, which every wave
     // has left (barrier): K(it+2) replaces K(it), V(it+1) replaces V(it-1).
     if constexpr (HAS_NEXT) {
-      if constexpr (DISTR) load_kraw(it + 2);
-      else dma_tile(k_rsrc, it + 2, dma_k, kx_buf(par));
+#ifndef DA_ABL_NOFUSE
+      // distr: raw K^T(it+3) replaces raw K^T(it+1), fused in the previous iteration; raw
+      // K^T(it+2), loaded during the previous iteration, is fused now into the buffer K_f^T(it)
+      // has left. Nothing in this iteration depends on the fusion: it runs beside the MFMAs.
+      if constexpr (DISTR) {
+        dma_kt_tile(it + 3, par ^ 1);
+        fuse(par);
+      }
+#endif
+      if constexpr (!DISTR) dma_tile(k_rsrc, it + 2, dma_k, kx_buf(par));
       dma_tile(v_rsrc, it + 1, dma_v, v_buf(par ^ 1));
     }
     if constexpr (HAS_NEXT) qk(par ^ 1, sn);
@@ -443,7 +453,7 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
         bf16x8 a = pop[(tt + mb + 1) & 3];
         (void)p0;
 #else
-        bf16x8 a = lds_read_tr_pair((const bf16*)p0, (const bf16*)(p0 + 8 * C::ROWB));
+        bf16x8 a = lds_read_tr_pair<bf16x8>(p0, p0 + 8 * C::ROWB);
 #endif
         oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pop[tt], oacc[mb], 0, 0, 0);
       }
@@ -482,11 +492,6 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
 #endif
     if constexpr (HAS_NEXT) {
       move_reference(mt_next);
-      if constexpr (DISTR) {   // raw K(it+2) -> gather layout -> fused tile K_f(it+2)
-        store_kraw();
-        __syncthreads();
-        fuse(par);
-      }
       dma_wait();              // this wave's direct loads have landed
     }
 #ifndef DA_ABL_NOBARRIER
@@ -497,22 +502,20 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   // ---- prologue: tiles 0 (K, V) and 1 (K) into LDS, scores of tile 0 ---------------------------
   dma_tile(v_rsrc, 0, dma_v, v_lds0);
   if constexpr (DISTR) {
-    load_kraw(0);
-    store_kraw();
+    dma_kt_tile(0, 0);
+    dma_kt_tile(1, 1);
+    dma_wait();
     __syncthreads();
     fuse(0);
-    if (n_tiles > 1) {
-      load_kraw(1);
-      __syncthreads();   // every wave is done gathering tile 0
-      store_kraw();
-      __syncthreads();
-      fuse(1);
-    }
+    fuse(1);
+    __syncthreads();   // raw tiles 0 and 1 are consumed
+    dma_kt_tile(2, 0);
+    dma_wait();
   } else {
     dma_tile(k_rsrc, 0, dma_k, kx_lds0);
     if (n_tiles > 1) dma_tile(k_rsrc, 1, dma_k, kx_lds1);
+    dma_wait();
   }
-  dma_wait();
   __syncthreads();
 
   const std::true_type yes;
@@ -520,6 +523,7 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   f32x16 s0[2], s1[2];
   qk(0, s0);
   move_reference(row_max(yes, 0, s0));
+  if constexpr (DISTR) __syncthreads();   // K_f^T(0) is rewritten by the first iteration's fusion
 
   // Tile it+1 needs no mask while it+1 < n_full. The main loop is unrolled by two so that the
   // two score register sets swap roles without copies.
@@ -554,26 +558,26 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
 
 template <int D, int BR, int KRED, bool DISTR>
 hipError_t launch_one(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
-                      const Problem& pb, hipStream_t stream) {
+                      const void* kt, const Problem& pb, hipStream_t stream) {
   const int Tq = (pb.N + BR - 1) / BR;
   const long long units = (long long)pb.B * pb.H * Tq;
   const float scale_log2e = pb.scale * 1.4426950408889634f;
   hipLaunchKernelGGL((attn_bf16_kernel<D, BR, KRED, DISTR>), dim3((unsigned)units), dim3(BR * 2), 0,
-                     stream, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, perm, pb.H,
-                     pb.Hkv, pb.N, Tq, pb.causal, scale_log2e, (int)units);
+                     stream, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, perm, (const f16*)kt,
+                     (pb.N + kBc - 1) / kBc * kBc, pb.H, pb.Hkv, pb.N, Tq, pb.causal, scale_log2e, (int)units);
   return hipGetLastError();
 }
 
 template <int D, int BR>
 hipError_t dispatch_kred(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
-                         const Problem& pb, int distr, hipStream_t stream) {
-  if (!distr) return launch_one<D, BR, D, false>(q, k, v, o, perm, pb, stream);
+                         const void* kt, const Problem& pb, int distr, hipStream_t stream) {
+  if (!distr) return launch_one<D, BR, D, false>(q, k, v, o, perm, kt, pb, stream);
   switch (pb.n_groups) {
-    case 16: return launch_one<D, BR, 16, true>(q, k, v, o, perm, pb, stream);
-    case 32: return launch_one<D, BR, 32, true>(q, k, v, o, perm, pb, stream);
-    case 64: return launch_one<D, BR, 64, true>(q, k, v, o, perm, pb, stream);
+    case 16: return launch_one<D, BR, 16, true>(q, k, v, o, perm, kt, pb, stream);
+    case 32: return launch_one<D, BR, 32, true>(q, k, v, o, perm, kt, pb, stream);
+    case 64: return launch_one<D, BR, 64, true>(q, k, v, o, perm, kt, pb, stream);
     case 128:
-      if constexpr (D == 128) return launch_one<D, BR, 128, true>(q, k, v, o, perm, pb, stream);
+      if constexpr (D == 128) return launch_one<D, BR, 128, true>(q, k, v, o, perm, kt, pb, stream);
       [[fallthrough]];
     default: return hipErrorInvalidValue;
   }
@@ -588,18 +592,18 @@ bool attn_bf16_supported(const Problem& pb, int distr) {
     const int kr = pb.n_groups;
     if (kr != 16 && kr != 32 && kr != 64 && kr != 128) return false;
     if (kr > pb.d || pb.d % kr != 0) return false;
-    if (kr / (pb.Br / 32) < 4) return false;   // each wave builds at least 4 fused slots per key row
   }
   return true;
 }
 
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
-                            const Problem& pb, int distr, hipStream_t stream) {
+                            const void* kt, const Problem& pb, int distr, hipStream_t stream) {
   if (!attn_bf16_supported(pb, distr)) return hipErrorInvalidValue;
-  if (pb.d == 64 && pb.Br == 64) return dispatch_kred<64, 64>(q, k, v, o, perm, pb, distr, stream);
-  if (pb.d == 64 && pb.Br == 128) return dispatch_kred<64, 128>(q, k, v, o, perm, pb, distr, stream);
-  if (pb.d == 128 && pb.Br == 64) return dispatch_kred<128, 64>(q, k, v, o, perm, pb, distr, stream);
-  return dispatch_kred<128, 128>(q, k, v, o, perm, pb, distr, stream);
+  if (distr && !kt) return hipErrorInvalidValue;
+  if (pb.d == 64 && pb.Br == 64) return dispatch_kred<64, 64>(q, k, v, o, perm, kt, pb, distr, stream);
+  if (pb.d == 64 && pb.Br == 128) return dispatch_kred<64, 128>(q, k, v, o, perm, kt, pb, distr, stream);
+  if (pb.d == 128 && pb.Br == 64) return dispatch_kred<128, 64>(q, k, v, o, perm, kt, pb, distr, stream);
+  return dispatch_kred<128, 128>(q, k, v, o, perm, kt, pb, distr, stream);
 }
 
 }  // namespace da

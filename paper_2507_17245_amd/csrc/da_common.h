@@ -40,9 +40,12 @@ struct Problem {
 // Launchers (defined next to their kernels). All return hipError_t of the launch.
 hipError_t launch_lsh_group(const void* q, int dtype, const Problem& pb, uint8_t* perm_out,
                             uint32_t* hash_out, hipStream_t stream);
-// distr != 0: S^ = Q_r K_f^T with the per-block permutation table `perm` [B][H][Tq][d].
+// K [B][Hkv][N][d] bf16 -> K^T [B][Hkv][d][Npad] half (Npad = N rounded up to kBc), for the distr path.
+hipError_t launch_kt_prepass(const void* k, void* kt, const Problem& pb, hipStream_t stream);
+// distr != 0: S^ = Q_r K_f^T with the per-block permutation table `perm` [B][H][Tq][d] and the
+// transposed keys `kt` written by launch_kt_prepass (k itself is then unused).
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
-                            const Problem& pb, int distr, hipStream_t stream);
+                            const void* kt, const Problem& pb, int distr, hipStream_t stream);
 hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
                            const Problem& pb, int distr, hipStream_t stream);
 bool attn_bf16_supported(const Problem& pb, int distr);

@@ -1,0 +1,74 @@
+// Key pre-pass of the DistrAttention path: K [B][Hkv][N][d] (bf16, d fastest) is rewritten once
+// per forward as K^T [B][Hkv][d][Npad] in half precision (keys fastest, Npad = N rounded up to
+// the 64-key tile, tail zero-filled).
+//
+// Why: the fusion step of Sec. 3.2 sums, for every (Q block, K tile) pair, the key channels of a
+// group chosen by that Q block's permutation. With keys fastest a channel is one contiguous
+// row, so "sum the group's channels" becomes whole-row vector adds (16-byte LDS reads, packed
+// half adds) instead of 2-byte gathers across a row-major tile. The pre-pass costs one read and
+// one write of K; the fusion it speeds up runs N/Br times over the same data.
+//
+// bf16 -> half is exact inside half's range (8 vs 11 significand bits). Values are clamped to
+// +-65504/G so that the sum of a group's G channels cannot overflow half.
+#include "da_common.h"
+
+namespace da {
+
+typedef _Float16 f16;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+
+constexpr int kKtThreads = 256;
+
+template <int D>
+__global__ __launch_bounds__(kKtThreads) void kt_prepass_kernel(const bf16* __restrict__ k,
+                                                                f16* __restrict__ kt, int N, int Npad,
+                                                                int Tk, float limit) {
+  // tile[key][channel], row stride D + 2 halves (odd number of dwords: the column reads below
+  // hit distinct banks)
+  __shared__ f16 tile[kBc][D + 2];
+  const int tid = threadIdx.x;
+  const int tk = blockIdx.x % Tk;
+  const size_t head = blockIdx.x / Tk;
+  const int n0 = tk * kBc;
+  const bf16* kh = k + head * (size_t)N * D;
+  f16* kth = kt + head * (size_t)D * Npad;
+
+  constexpr int CH = D / 8;   // 16-byte chunks per key row
+  for (int id = tid; id < kBc * CH; id += kKtThreads) {
+    const int row = id / CH, col = (id % CH) * 8;
+    bf16x8 x;
+    if (n0 + row < N) x = *(const bf16x8*)(kh + (size_t)(n0 + row) * D + col);
+    else
+#pragma unroll
+      for (int j = 0; j < 8; ++j) x[j] = (bf16)0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      tile[row][col + j] = (f16)__builtin_amdgcn_fmed3f((float)x[j], -limit, limit);
+  }
+  __syncthreads();
+  // output chunk (channel c, 8 consecutive keys)
+  for (int id = tid; id < D * (kBc / 8); id += kKtThreads) {
+    const int c = id / (kBc / 8), kc = (id % (kBc / 8)) * 8;
+    f16x8 y;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) y[j] = tile[kc + j][c];
+    *(f16x8*)(kth + (size_t)c * Npad + n0 + kc) = y;
+  }
+}
+
+hipError_t launch_kt_prepass(const void* k, void* kt, const Problem& pb, hipStream_t stream) {
+  const int Tk = (pb.N + kBc - 1) / kBc;
+  const int Npad = Tk * kBc;
+  const long long units = (long long)pb.B * pb.Hkv * Tk;
+  const float limit = 65504.0f / (float)(pb.d / pb.n_groups);
+  dim3 grid((unsigned)units), block(kKtThreads);
+  if (pb.d == 64)
+    hipLaunchKernelGGL((kt_prepass_kernel<64>), grid, block, 0, stream, (const bf16*)k, (f16*)kt, pb.N, Npad, Tk, limit);
+  else if (pb.d == 128)
+    hipLaunchKernelGGL((kt_prepass_kernel<128>), grid, block, 0, stream, (const bf16*)k, (f16*)kt, pb.N, Npad, Tk, limit);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+}  // namespace da
