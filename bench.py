@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the DistrAttention forward pass on one MI355X.
 
-A step is one pass of the whole hot path -- LSH hash-and-group kernel, then the attention
-kernel with in-LDS key fusion -- over one batch of synthetic input already resident in HBM.
+A step is one pass of the whole hot path -- LSH hash-and-group kernel, key pre-pass, then the
+attention kernel with in-LDS key fusion -- over one batch of synthetic input already resident in HBM.
 The headline workload is the long-sequence configuration (the largest one of the five); the
 other configurations are measured in the same run and reported inside the same JSON line
 under "configs". The exact-attention kernel, built the same way, is timed beside it.
@@ -76,7 +76,6 @@ def main():
         common = dict(Br=cfg.Br, Bc=cfg.Bc, causal=cfg.causal, n_planes=cfg.n_planes, lsh_seed=cfg.lsh_seed)
         p_full = da.make_params(q, k, v, n_groups=n_groups, **common)
         p_lsh = da.make_params(q, k, v, n_groups=n_groups, perm_out=perm, **common)
-        p_attn = da.make_params(q, k, v, n_groups=n_groups, perm_in=perm, **common)
         p_ex = da.make_params(q, k, v, **common)
         step = lambda: da.distr_attn_fwd_ex(q, k, v, o, p_full)
         for _ in range(warmup):
@@ -87,8 +86,17 @@ def main():
             step()
         torch.cuda.synchronize()
         ms_step = (time.perf_counter() - t0) * 1e3 / steps
+        # the three kernels of the step, one by one
         da.distr_attn_lsh_group(q, p_lsh)
         ms_lsh = ev_time(lambda: da.distr_attn_lsh_group(q, p_lsh), steps)
+        ms_prepass = 0.0
+        kt = None
+        if cfg.dtype == "bf16":
+            kt = torch.empty(da.distr_attn_kt_bytes(p_full), dtype=torch.uint8, device=dev)
+            da.distr_attn_key_prepass(k, kt, p_full)
+            ms_prepass = ev_time(lambda: da.distr_attn_key_prepass(k, kt, p_full), steps)
+        p_attn = da.make_params(q, k, v, n_groups=n_groups, perm_in=perm, kt_in=kt, **common)
+        da.distr_attn_fwd_ex(q, k, v, o, p_attn)
         ms_attn = ev_time(lambda: da.distr_attn_fwd_ex(q, k, v, o, p_attn), steps)
         for _ in range(warmup):
             da.distr_attn_exact_fwd_ex(q, k, v, o_ex, p_ex)
@@ -101,7 +109,7 @@ def main():
             "dtype": cfg.dtype, "causal": cfg.causal, "Br": cfg.Br, "Bc": cfg.Bc, "n_groups": n_groups,
             "ms_per_forward": ms_step, "eff_tflops": flops / ms_step / 1e9,
             "pct_bf16_peak": 100.0 * flops / ms_step / 1e9 / PEAK_BF16_TFLOPS,
-            "ms_lsh_kernel": ms_lsh, "ms_attn_kernel": ms_attn,
+            "ms_lsh_kernel": ms_lsh, "ms_key_prepass_kernel": ms_prepass, "ms_attn_kernel": ms_attn,
             "ms_exact_kernel": ms_exact, "exact_eff_tflops": flops / ms_exact / 1e9,
             "speedup_vs_exact_kernel": ms_exact / ms_step,
             "attn_kernel_algorithmic_flops": 2.0 * pairs * (n_groups + cfg.d),

@@ -56,13 +56,15 @@ typedef struct {
   int gray_mode;        /* Gray map of the sign word (Sec. 3.2): 0 = position of the word in the Gray
                            sequence, 1 = Gray code of the word                                     */
   void *stream;         /* hipStream_t; NULL = the stream set by distr_attn_set_stream (default: null stream) */
-  void *workspace;      /* device scratch of >= distr_attn_workspace_bytes(); NULL = library-owned,
-                           grown on demand (hipMalloc on first use / growth)                        */
+  void *workspace;      /* device scratch of >= distr_attn_workspace_bytes(), 256-byte aligned; NULL =
+                           library-owned, grown on demand (hipMalloc on first use / growth)        */
   size_t workspace_bytes;
   uint8_t *perm_out;    /* optional device [B][H][Tq][d]: channel at sorted position s of each block */
   uint32_t *hash_out;   /* optional device [B][H][Tq][d]: hash of each channel of each block          */
   const uint8_t *perm_in; /* optional device [B][H][Tq][d]: use this grouping and skip the LSH stage
                              (each row must be a permutation of 0..d-1; it is not checked)          */
+  const void *kt_in;      /* optional device buffer written by distr_attn_key_prepass for this k and
+                             n_groups: skip the key pre-pass (bf16 only)                            */
 } da_params;
 
 /*
@@ -90,7 +92,18 @@ int distr_attn_exact_fwd_ex(const void *q, const void *k, const void *v, void *o
  */
 int distr_attn_lsh_group(const void *q, const da_params *p);
 
-/* Bytes of device scratch distr_attn_fwd_ex needs for p (0 on invalid p). */
+/*
+ * Key pre-pass of the bf16 DistrAttention path alone: k [B][Hkv][N][d] bf16 -> kt_out
+ * [B][Hkv][d][Npad] half, keys fastest, Npad = N rounded up to 64, tail zero-filled, values
+ * clamped to +-65504/G* so that a group's sum (Sec. 3.2 fusion) stays finite in half. The fusion
+ * then adds whole channel rows. distr_attn_fwd_ex runs it into its workspace unless kt_in is given.
+ * kt_out: device, distr_attn_kt_bytes(p) bytes, 256-byte aligned.
+ */
+int distr_attn_key_prepass(const void *k, void *kt_out, const da_params *p);
+size_t distr_attn_kt_bytes(const da_params *p);
+
+/* Bytes of device scratch distr_attn_fwd_ex needs for p: permutation table + transposed keys
+ * (0 on invalid p). */
 size_t distr_attn_workspace_bytes(const da_params *p);
 
 /*

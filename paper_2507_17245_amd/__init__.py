@@ -16,7 +16,8 @@ DA_BF16, DA_F32 = 0, 1
 
 EXPORTS = (
     "distr_attn_fwd", "distr_attn_exact_fwd", "distr_attn_fwd_ex", "distr_attn_exact_fwd_ex",
-    "distr_attn_lsh_group", "distr_attn_workspace_bytes", "distr_attn_hyperplanes",
+    "distr_attn_lsh_group", "distr_attn_key_prepass", "distr_attn_kt_bytes",
+    "distr_attn_workspace_bytes", "distr_attn_hyperplanes",
     "distr_attn_set_stream", "distr_attn_release", "distr_attn_last_error", "distr_attn_version",
 )
 
@@ -30,7 +31,7 @@ class DaParams(ctypes.Structure):
         ("n_planes", ctypes.c_int), ("softmax_scale", ctypes.c_float), ("gray_mode", ctypes.c_int),
         ("stream", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_size_t), ("perm_out", ctypes.c_void_p),
-        ("hash_out", ctypes.c_void_p), ("perm_in", ctypes.c_void_p),
+        ("hash_out", ctypes.c_void_p), ("perm_in", ctypes.c_void_p), ("kt_in", ctypes.c_void_p),
     ]
 
 
@@ -56,8 +57,10 @@ def lib():
         for name in ("distr_attn_fwd_ex", "distr_attn_exact_fwd_ex"):
             getattr(L, name).argtypes = [vp, vp, vp, vp, ctypes.POINTER(DaParams)]
         L.distr_attn_lsh_group.argtypes = [vp, ctypes.POINTER(DaParams)]
-        L.distr_attn_workspace_bytes.argtypes = [ctypes.POINTER(DaParams)]
-        L.distr_attn_workspace_bytes.restype = ctypes.c_size_t
+        L.distr_attn_key_prepass.argtypes = [vp, vp, ctypes.POINTER(DaParams)]
+        for name in ("distr_attn_workspace_bytes", "distr_attn_kt_bytes"):
+            getattr(L, name).argtypes = [ctypes.POINTER(DaParams)]
+            getattr(L, name).restype = ctypes.c_size_t
         L.distr_attn_hyperplanes.argtypes = [u64, ci, ci, ctypes.POINTER(ctypes.c_float)]
         L.distr_attn_set_stream.argtypes = [vp]
         L.distr_attn_last_error.restype = ctypes.c_char_p
@@ -105,7 +108,7 @@ def _shapes(q, k, v):
 
 def make_params(q, k, v, Br, Bc=64, n_groups=None, causal=False, lsh_seed=0, n_planes=0,
                 softmax_scale=0.0, gray_mode=0, workspace=None, perm_out=None, hash_out=None,
-                perm_in=None):
+                perm_in=None, kt_in=None):
     B, H, Hkv, N, d = _shapes(q, k, v)
     p = DaParams()
     p.B, p.H, p.Hkv, p.N, p.d, p.Br, p.Bc = B, H, Hkv, N, d, Br, Bc
@@ -123,6 +126,7 @@ def make_params(q, k, v, Br, Bc=64, n_groups=None, causal=False, lsh_seed=0, n_p
     p.perm_out = perm_out.data_ptr() if perm_out is not None else None
     p.hash_out = hash_out.data_ptr() if hash_out is not None else None
     p.perm_in = perm_in.data_ptr() if perm_in is not None else None
+    p.kt_in = kt_in.data_ptr() if kt_in is not None else None
     return p
 
 
@@ -159,6 +163,15 @@ def distr_attn_exact_fwd_ex(q, k, v, o, params):
 
 def distr_attn_lsh_group(q, params):
     _check(lib().distr_attn_lsh_group(_ptr(q), ctypes.byref(params)))
+
+
+def distr_attn_key_prepass(k, kt_out, params):
+    _check(lib().distr_attn_key_prepass(_ptr(k), _ptr(kt_out), ctypes.byref(params)))
+    return kt_out
+
+
+def distr_attn_kt_bytes(params):
+    return int(lib().distr_attn_kt_bytes(ctypes.byref(params)))
 
 
 def distr_attn_workspace_bytes(params):

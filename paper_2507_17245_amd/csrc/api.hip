@@ -141,6 +141,17 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
                 "got d=%d Br=%d n_groups=%d", p->d, p->Br, p->n_groups);
   const uint8_t* perm = nullptr;
   void* kt = nullptr;
+  // Groups of one channel (G* = 1): S^ = Q_r K_f^T is Q K^T with its terms taken in the sorted
+  // channel order (Sec. 3.1: one column per group reproduces S). The bf16 path then runs the
+  // exact kernel; the LSH stage still runs if the caller asked for its tables.
+  const bool trivial_groups = distr && r.dtype == DA_BF16 && p->n_groups == p->d;
+  if (trivial_groups) {
+    if (!p->perm_in && (p->perm_out || p->hash_out)) {
+      rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, p->perm_out, p->hash_out, r.stream), "lsh_group launch");
+      if (rc) return rc;
+    }
+    distr = false;
+  }
   if (distr) {
     uint8_t* table = nullptr;
     rc = get_scratch(p, r, p->perm_in == nullptr, &table, &kt);
@@ -152,7 +163,10 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
       if (rc) return rc;
       perm = table;
     }
-    if (r.dtype == DA_BF16) {
+    if (r.dtype == DA_BF16 && p->kt_in) {
+      if (((uintptr_t)p->kt_in & 255u) != 0) return fail(DA_ERR_INVALID_ARG, "kt_in must be 256-byte aligned");
+      kt = const_cast<void*>(p->kt_in);
+    } else if (r.dtype == DA_BF16) {
       rc = check_launch(da::launch_kt_prepass(k, kt, r.pb, r.stream), "key pre-pass launch");
       if (rc) return rc;
     }
@@ -202,6 +216,23 @@ int distr_attn_lsh_group(const void* q, const da_params* p) {
   if (!q) return fail(DA_ERR_INVALID_ARG, "q must be non-null");
   if (!p->perm_out && !p->hash_out) return fail(DA_ERR_INVALID_ARG, "perm_out or hash_out must be given");
   return check_launch(da::launch_lsh_group(q, r.dtype, r.pb, p->perm_out, p->hash_out, r.stream), "lsh_group launch");
+}
+
+int distr_attn_key_prepass(const void* k, void* kt_out, const da_params* p) {
+  Resolved r;
+  int rc = resolve(p, true, &r);
+  if (rc) return rc;
+  if (!k || !kt_out) return fail(DA_ERR_INVALID_ARG, "k and kt_out must be non-null");
+  if (r.dtype != DA_BF16) return fail(DA_ERR_UNSUPPORTED, "the key pre-pass belongs to the bf16 path");
+  if (((uintptr_t)k & 15u) != 0 || ((uintptr_t)kt_out & 255u) != 0)
+    return fail(DA_ERR_INVALID_ARG, "k must be 16-byte and kt_out 256-byte aligned");
+  return check_launch(da::launch_kt_prepass(k, kt_out, r.pb, r.stream), "key pre-pass launch");
+}
+
+size_t distr_attn_kt_bytes(const da_params* p) {
+  Resolved r;
+  if (resolve(p, true, &r)) return 0;
+  return kt_bytes(r);
 }
 
 size_t distr_attn_workspace_bytes(const da_params* p) {

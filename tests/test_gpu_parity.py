@@ -131,3 +131,36 @@ def test_runs_are_deterministic_and_short_form_agrees():
     da.distr_attn_fwd_ex(tq, tk, tv, o2, p)
     torch.cuda.synchronize()
     assert torch.equal(o2, o)
+
+
+def test_key_prepass_is_an_exact_transpose_and_kt_in_is_honoured():
+    import torch
+    import paper_2507_17245_amd as da
+    U = _util()
+    cfg = small("mid", B=2, H=4, Hkv=2, N=200)
+    q, k, v = W.make(cfg)
+    tq, tk, tv = (U.to_dev(x, "bf16") for x in (q, k, v))
+    p = da.make_params(tq, tk, tv, Br=cfg.Br, n_groups=cfg.n_groups)
+    kt = torch.zeros(da.distr_attn_kt_bytes(p), dtype=torch.uint8, device="cuda")
+    da.distr_attn_key_prepass(tk, kt, p)
+    torch.cuda.synchronize()
+    npad = (cfg.N + 63) // 64 * 64
+    got = kt[:cfg.B * cfg.Hkv * cfg.d * npad * 2].view(torch.float16).view(cfg.B, cfg.Hkv, cfg.d, npad).float().cpu().numpy()
+    assert np.array_equal(got[..., :cfg.N], np.swapaxes(k, 2, 3))      # bf16 -> half is exact here
+    assert not got[..., cfg.N:].any()                                  # zero-filled tail
+    # values beyond half's range are clamped to +-65504 / G*
+    big = tk.clone()
+    big[0, 0, 0, 0] = 1e6
+    big[0, 0, 1, 1] = -1e6
+    da.distr_attn_key_prepass(big, kt, p)
+    torch.cuda.synchronize()
+    g2 = kt[:cfg.B * cfg.Hkv * cfg.d * npad * 2].view(torch.float16).view(cfg.B, cfg.Hkv, cfg.d, npad)
+    lim = 65504.0 / (cfg.d // cfg.n_groups)
+    assert float(g2[0, 0, 0, 0]) == np.float16(lim) and float(g2[0, 0, 1, 1]) == -np.float16(lim)
+    # a forward with caller-provided kt equals the forward that runs the pre-pass itself
+    da.distr_attn_key_prepass(tk, kt, p)
+    o1, o2 = torch.empty_like(tq), torch.empty_like(tq)
+    da.distr_attn_fwd_ex(tq, tk, tv, o1, p)
+    da.distr_attn_fwd_ex(tq, tk, tv, o2, da.make_params(tq, tk, tv, Br=cfg.Br, n_groups=cfg.n_groups, kt_in=kt))
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
