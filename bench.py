@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--workload", default="long", help="headline configuration (workloads.CONFIGS)")
     ap.add_argument("--only", action="store_true", help="measure the headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="only run a plain device-to-device copy of MIB mebibytes (5 times): the known-size "
+                         "kernel against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures ONE GPU (one process, one device); run with --gpus 1. "
@@ -53,6 +56,15 @@ def main():
     da.lib()   # fail loudly if the HIP library is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.calibrate_copy:
+        n = args.calibrate_copy << 20
+        src = torch.arange(n // 4, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 5}))
+        return
 
     def to_dev(x, dtype):
         t = torch.from_numpy(x).to(dev)
@@ -148,10 +160,22 @@ def main():
     head = results[f"{args.workload}_k{head_cfg.n_groups}"]
 
     # ---- roofline of the dominant kernel (the attention kernel of the distr path) ---------------
+    # HBM traffic per launch comes from separate rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled
+    # by a plain copy of known size); the committed summary carries the figure for its workload.
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "attn_bf16_long_hbm_traffic.md")) as f:
+            for line in f:
+                if line.startswith("bench-traffic:"):
+                    rec = json.loads(line.split(":", 1)[1])
+                    if rec.get("workload") == args.workload:
+                        traffic = rec["hbm_bytes_per_launch"]
+    except OSError:
+        pass
     achieved = head["attn_kernel_algorithmic_flops"] / (head["ms_attn_kernel"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "attn_bf16_kernel (distr)", "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "traffic": None,
+                "traffic": traffic,
                 "exact_kernel_achieved": head["exact_kernel_algorithmic_flops"] / (head["ms_exact_kernel"] * 1e-3) / 1e12}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload --------
