@@ -344,6 +344,13 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
         kx8 a;
 #ifdef DA_ABL_NOKREAD
         a = qop[(s + 1) % C::KSTEPS];
+#elif defined(DA_ABL_HALFREAD)
+        if (mb == 1) a = qop[(s + 1) % C::KSTEPS]; else
+        if constexpr (DISTR)
+          a = lds_read_tr_pair<kx8>(base + ka_off[mb * 2] + s * 16 * C::KTROWB,
+                                    base + ka_off[mb * 2 + 1] + s * 16 * C::KTROWB);
+        else
+          a = *(const kx8*)(base + ka_off[s] + mb * 32 * C::ROWB);
 #else
         if constexpr (DISTR)
           a = lds_read_tr_pair<kx8>(base + ka_off[mb * 2] + s * 16 * C::KTROWB,
@@ -452,6 +459,8 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
 #ifdef DA_ABL_NOVREAD
         bf16x8 a = pop[(tt + mb + 1) & 3];
         (void)p0;
+#elif defined(DA_ABL_HALFREAD)
+        bf16x8 a = (mb & 1) ? pop[(tt + mb + 1) & 3] : lds_read_tr_pair<bf16x8>(p0, p0 + 8 * C::ROWB);
 #else
         bf16x8 a = lds_read_tr_pair<bf16x8>(p0, p0 + 8 * C::ROWB);
 #endif
@@ -467,9 +476,12 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
     {
       constexpr int N_QK = HAS_NEXT ? 2 * C::KSTEPS : 0;
       constexpr int N_PV = D / 8;
-      constexpr int VALU_PER_MFMA = (150 + N_QK + N_PV - 1) / (N_QK + N_PV);
+      constexpr int VALU_PER_MFMA = ((DA_HINTS == 2 ? 118 : 150) + N_QK + N_PV - 1) / (N_QK + N_PV);
       constexpr int PF = DA_KPF < N_QK ? DA_KPF : N_QK;
       __builtin_amdgcn_sched_group_barrier(0x100, HAS_NEXT ? PF : 2 * DA_KPF, 0);
+#if DA_HINTS == 2   // vector work first, while the first operands travel
+      __builtin_amdgcn_sched_group_barrier(0x402, 32, 0);
+#endif
 #pragma unroll
       for (int i = 0; i < N_QK - PF; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one score MFMA
@@ -508,22 +520,24 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
     __syncthreads();
     fuse(0);
     fuse(1);
-    __syncthreads();   // raw tiles 0 and 1 are consumed
-    dma_kt_tile(2, 0);
-    dma_wait();
+    __syncthreads();   // raw tiles 0 and 1 are consumed, K_f^T(0) and K_f^T(1) are visible
+    dma_kt_tile(2, 0);   // lands while the scores of tile 0 are computed
   } else {
     dma_tile(k_rsrc, 0, dma_k, kx_lds0);
     if (n_tiles > 1) dma_tile(k_rsrc, 1, dma_k, kx_lds1);
     dma_wait();
+    __syncthreads();
   }
-  __syncthreads();
 
   const std::true_type yes;
   const std::false_type no;
   f32x16 s0[2], s1[2];
   qk(0, s0);
   move_reference(row_max(yes, 0, s0));
-  if constexpr (DISTR) __syncthreads();   // K_f^T(0) is rewritten by the first iteration's fusion
+  if constexpr (DISTR) {
+    dma_wait();
+    __syncthreads();   // raw K^T(2) is in; K_f^T(0) may be rewritten by the first iteration's fusion
+  }
 
   // Tile it+1 needs no mask while it+1 < n_full. The main loop is unrolled by two so that the
   // two score register sets swap roles without copies.
