@@ -14,11 +14,16 @@
 // contraction index kv is enumerated in the accumulator's order on both operands.
 //   exact:  Kx = K tile,  Qx = Q,    contraction over d channels
 //   distr:  Kx = K_f tile (Sec. 3.2 fusion: sum of the group's K channels, built once per
-//           (Q block, K tile) in LDS by all waves together), Qx = Q_r (sampling: the group's
-//           first channel in sorted order, gathered once per Q block), contraction over
-//           n_groups = d / G*.
-// Online softmax (running max, running sum, rescaled accumulator) follows the block-wise
-// scheme of Sec. 2.2.2 in the exp2 domain.
+//           (Q block, K tile) in LDS by all waves together from a transposed half-precision
+//           copy of K, as whole-row packed adds), Qx = Q_r (sampling: the group's first channel
+//           in sorted order, gathered once per Q block), contraction over n_groups = d / G*,
+//           on the f16 matrix path.
+// Online softmax (reference max, row sum, rescaled accumulator) follows the block-wise scheme of
+// Sec. 2.2.2 in the exp2 domain.
+//
+// Pipeline (one barrier per tile): tiles reach LDS by direct global->LDS loads two tiles (K) /
+// one tile (V) ahead; while the vector ALUs exponentiate tile i the matrix pipe computes the
+// scores of tile i+1; P.V of tile i runs beside the row maximum of tile i+1.
 #include <type_traits>
 
 #include "da_common.h"
@@ -29,7 +34,6 @@ namespace {
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef _Float16 f16;
-typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 
 // Largest finite half; sampled queries and fused keys of the distr path are clamped to it.
@@ -118,6 +122,11 @@ struct Cfg {
 #ifndef DA_WAVES_PER_EU
 #define DA_WAVES_PER_EU 2   // occupancy target (waves per SIMD) given to the register allocator
 #endif
+// Ablation switches (never defined in the shipped build; results are wrong with any of them):
+// DA_ABL_NOKREAD / DA_ABL_NOVREAD replace the LDS operand reads of the score / P.V product by
+// registers, DA_ABL_NOEXP drops the exponentials, DA_ABL_NOBARRIER the per-tile barrier,
+// DA_ABL_NOFUSE the per-tile key fusion. Timing the kernel with one of them removed tells what
+// that part costs; every access stays in bounds and every loop keeps its trip count.
 
 // Rows whose running maximum moved by less than this (in log2 units) keep their old reference
 // maximum: P is then at most 2^kTau, the sums stay exact ratios, and the accumulator rescale
@@ -183,7 +192,7 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   // ---- Q operands, held for the whole inner loop ------------------------------------------
   // distr: the reduced product runs on the f16 matrix path. A bf16 value converts to half
   // exactly (8 vs 11 significand bits) inside half's exponent range, and the fused keys, rounded
-  // once from their float sum, keep 3 more bits than bf16 would: with bf16 K_f the logit error
+  // to half from the sum of such values, keep 3 more bits than bf16 would: with bf16 K_f the logit error
   // on inputs with heavy-tailed channel scales exceeds what the output tolerance allows.
   kx8 qop[C::KSTEPS];
   if constexpr (DISTR) {
@@ -227,7 +236,7 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   // tiles [0, n_full) need no masking for any row of the block
   const int n_full = causal ? min(r0, N) / kBc : N / kBc;
 
-  // ---- staging: global -> registers -> LDS ---------------------------------------------------
+  // ---- tile loads: global -> LDS ---------------------------------------------------------------
   // K and V rows are fetched through buffer descriptors: the per-lane byte offset inside a
   // tile is fixed, the tile advances through the scalar offset, and rows past the end of the
   // head read as zero (hardware range check), so a tile costs no address arithmetic.
@@ -344,13 +353,6 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
         kx8 a;
 #ifdef DA_ABL_NOKREAD
         a = qop[(s + 1) % C::KSTEPS];
-#elif defined(DA_ABL_HALFREAD)
-        if (mb == 1) a = qop[(s + 1) % C::KSTEPS]; else
-        if constexpr (DISTR)
-          a = lds_read_tr_pair<kx8>(base + ka_off[mb * 2] + s * 16 * C::KTROWB,
-                                    base + ka_off[mb * 2 + 1] + s * 16 * C::KTROWB);
-        else
-          a = *(const kx8*)(base + ka_off[s] + mb * 32 * C::ROWB);
 #else
         if constexpr (DISTR)
           a = lds_read_tr_pair<kx8>(base + ka_off[mb * 2] + s * 16 * C::KTROWB,
@@ -459,8 +461,6 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
 #ifdef DA_ABL_NOVREAD
         bf16x8 a = pop[(tt + mb + 1) & 3];
         (void)p0;
-#elif defined(DA_ABL_HALFREAD)
-        bf16x8 a = (mb & 1) ? pop[(tt + mb + 1) & 3] : lds_read_tr_pair<bf16x8>(p0, p0 + 8 * C::ROWB);
 #else
         bf16x8 a = lds_read_tr_pair<bf16x8>(p0, p0 + 8 * C::ROWB);
 #endif
