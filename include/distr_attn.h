@@ -41,7 +41,9 @@ typedef enum { DA_BF16 = 0, DA_F32 = 1 } da_dtype;
  *
  * Supported by the kernels: d in {64, 128}; Br in {64, 128}; Bc = 64; n_groups a multiple
  * of 16 for bf16 (the MFMA contraction step) and any divisor of d for float; 1 <= n_planes <= 32;
- * N >= 1 arbitrary (ragged last blocks are masked).
+ * N >= 1 arbitrary (ragged last blocks are masked), N * d * 4 < 2^31; at most 2^31 - 1 query blocks.
+ * bf16 DistrAttention path: |q| and |k| beyond 65504 / G* are clamped (the reduced product runs in
+ * half precision).
  */
 typedef struct {
   int B, H, Hkv, N, d;
@@ -57,7 +59,9 @@ typedef struct {
                            sequence, 1 = Gray code of the word                                     */
   void *stream;         /* hipStream_t; NULL = the stream set by distr_attn_set_stream (default: null stream) */
   void *workspace;      /* device scratch of >= distr_attn_workspace_bytes(), 256-byte aligned; NULL =
-                           library-owned, grown on demand (hipMalloc on first use / growth)        */
+                           library-owned, one per device, grown on demand (hipMalloc on first use /
+                           growth, after a device synchronise). Calls that may overlap in time on
+                           different streams must each bring their own workspace.                   */
   size_t workspace_bytes;
   uint8_t *perm_out;    /* optional device [B][H][Tq][d]: channel at sorted position s of each block */
   uint32_t *hash_out;   /* optional device [B][H][Tq][d]: hash of each channel of each block          */

@@ -54,6 +54,8 @@ int resolve(const da_params* p, bool need_groups, Resolved* out) {
   if ((long long)p->B * p->H * ((p->N + p->Br - 1) / p->Br) > 0x7fffffffLL)
     return fail(DA_ERR_UNSUPPORTED, "more than 2^31-1 query blocks");
   // limits of the kernels
+  if ((long long)p->N * p->d * 4 > 0x7fffffffLL)
+    return fail(DA_ERR_UNSUPPORTED, "N * d = %lld: one head must stay below 2 GiB (32-bit tile offsets)", (long long)p->N * p->d);
   if (p->d != 64 && p->d != 128) return fail(DA_ERR_UNSUPPORTED, "d = %d: kernels are built for d in {64, 128}", p->d);
   if (p->Br != 64 && p->Br != 128) return fail(DA_ERR_UNSUPPORTED, "Br = %d: kernels are built for Br in {64, 128}", p->Br);
   if (p->Bc != 64) return fail(DA_ERR_UNSUPPORTED, "Bc = %d: kernels are built for Bc = 64", p->Bc);

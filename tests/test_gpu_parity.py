@@ -33,6 +33,9 @@ SMALL_CASES = [
     small("vit", B=1, H=2, Hkv=1, N=130, n_groups=64, Br=128, causal=True),
     small("tiny"),                                                   # float path, full config
     small("tiny", N=150, d=128, n_groups=32, Br=128, causal=True, recipe="normal"),
+    small("tiny", N=100, n_groups=1, recipe="normal"),               # float path, one group of all channels
+    small("tiny", N=100, n_groups=64, recipe="normal", causal=True), # float path, groups of one channel
+    small("tiny", N=70, n_groups=4, H=4, Hkv=2, B=2, recipe="normal"),
 ]
 
 
@@ -164,3 +167,29 @@ def test_key_prepass_is_an_exact_transpose_and_kt_in_is_honoured():
     da.distr_attn_fwd_ex(tq, tk, tv, o2, da.make_params(tq, tk, tv, Br=cfg.Br, n_groups=cfg.n_groups, kt_in=kt))
     torch.cuda.synchronize()
     assert torch.equal(o1, o2)
+
+
+def test_side_stream_and_back_to_back_calls():
+    """Calls are asynchronous on the given stream: several forwards queued on a side stream without
+    host synchronisation in between (library-owned workspace reused) give the same results as
+    isolated calls."""
+    import torch
+    import paper_2507_17245_amd as da
+    U = _util()
+    cfgs = [small("mid", B=1, H=2, Hkv=2, N=300, n_groups=64), small("vit", B=1, H=4, Hkv=4, N=130)]
+    data = [W.make(c) for c in cfgs]
+    expect = [U.run_gpu(c, *d, distr=True)[0] for c, d in zip(cfgs, data)]
+    side = torch.cuda.Stream()
+    outs = []
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            for c, (q, k, v) in zip(cfgs, data):
+                tq, tk, tv = (U.to_dev(x, "bf16") for x in (q, k, v))
+                o = torch.empty_like(tq)
+                p = da.make_params(tq, tk, tv, Br=c.Br, n_groups=c.n_groups, causal=c.causal, lsh_seed=c.lsh_seed)
+                assert p.stream == side.cuda_stream
+                da.distr_attn_fwd_ex(tq, tk, tv, o, p)
+                outs.append(o)
+    side.synchronize()
+    for i, o in enumerate(outs):
+        assert np.array_equal(o.float().cpu().numpy().astype(np.float64), expect[i % 2])

@@ -72,6 +72,7 @@ FAKE_O = ctypes.c_void_p(0x2000)
     (dict(Bc=128), da.DA_ERR_UNSUPPORTED),
     (dict(n_planes=33), da.DA_ERR_UNSUPPORTED),
     (dict(n_groups=8), da.DA_ERR_UNSUPPORTED),            # below the MFMA contraction step
+    (dict(N=1 << 23, d=128, n_groups=64), da.DA_ERR_UNSUPPORTED),   # a head of 4 GiB: 32-bit tile offsets
 ])
 def test_bad_arguments_fail_on_the_host(kw, code):
     p = _params(**kw)
