@@ -80,6 +80,25 @@ __device__ inline float half_swap_sum(float x) {
   return lo + hi;
 }
 
+// Swizzle of the 32-byte segments of a tile that is read with transposing accesses
+// (ds_read_b64_tr_b16): the LDS serves 32 lanes of such a read per cycle, which address the rows
+// r..r+3 (r a multiple of 4) at two adjacent 32-byte segments, 4 lanes x 8 bytes per row and
+// segment. v_swizzle spreads those 4 rows x 2 segments over all 64 banks (no conflict cycles in
+// the hardware counters): with 256-byte rows the row picks one of four segment pairs, with
+// 128-byte rows two consecutive rows already sit in opposite bank halves and only rows of equal
+// parity need separating.
+template <int ROW_BYTES>
+__device__ inline int v_swizzle(int row) {
+  static_assert(ROW_BYTES == 256 || ROW_BYTES == 128, "row length");
+  return ROW_BYTES == 256 ? ((row & 3) << 1) : (row & 2);
+}
+// The fused tile K_f^T (128-byte rows) keeps a swizzle that leaves a two-way conflict on its
+// transposing reads: those reads are limited by the return path, not by the banks (same
+// throughput in a micro-benchmark), and the kernels built with the conflict-free form were
+// measured 2 % (d = 128) to 25 % (d = 64, through a change of register count and residency)
+// slower.
+__device__ inline int kf_swizzle(int row) { return (row >> 1) & 3; }
+
 template <int D, int BR, int KRED, bool DISTR>
 struct Cfg {
   static constexpr int NW = BR / 32;              // wavefronts per workgroup
@@ -94,9 +113,11 @@ struct Cfg {
   //      K (read with 16-byte accesses, 16 lanes = 16 rows at one logical chunk):
   //          chunk' = chunk ^ (row & 15)            (D = 128: 16 chunks per row)
   //          chunk' = chunk ^ ((row >> 1) & 7)      (D = 64: 8 chunks per row, two rows per 256 B)
-  //      V (read with transposing 8-byte accesses, 4 rows x 32 bytes per 16 lanes):
-  //          32-byte segment' = segment ^ (row & 7)         (D = 128)
-  //          32-byte segment' = segment ^ ((row >> 1) & 3)  (D = 64)
+  //      V (read with transposing 8-byte accesses; the LDS serves 32 lanes per cycle, which
+  //      address 4 rows x 2 adjacent 32-byte segments and must cover all 256 bytes of banks):
+  //          32-byte segment' = segment ^ 2*(row & 3)       (D = 128: 8 segments per row)
+  //          32-byte segment' = segment ^ (row & 2)         (D = 64: 4 segments per row, rows of
+  //                                                          opposite parity sit in opposite bank halves)
   //    The loading lane fetches the global chunk that belongs at its LDS position.
   //  * distr path: the keys arrive transposed and in half precision (K^T, one row of 64 keys =
   //    128 bytes per channel, written once per forward by the key pre-pass). The raw tile is
@@ -163,14 +184,25 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   const int lq = lane & 31;   // query row of this lane inside the wave's 32 rows
   const int hh = lane >> 5;   // which half of each 8-wide contraction chunk this lane feeds
 
-  // Workgroup -> (batch*head, Q block). Consecutive workgroup ids go round-robin over the 8
-  // XCDs; remap so that each XCD walks a contiguous range of units and the Q blocks of one
-  // head share that XCD's L2 for K and V. Causal blocks are taken longest first.
+  // Workgroup -> (batch*head, Q block). Consecutive workgroup ids go round-robin over the 8 XCDs.
   int unit = blockIdx.x;
-  if ((total_units & 7) == 0) unit = (blockIdx.x & 7) * (total_units >> 3) + (blockIdx.x >> 3);
-  const int bh = unit / Tq;
-  int t = unit % Tq;
-  if (causal) t = Tq - 1 - t;
+  int bh, t;
+  if (causal) {
+    // Blocks differ up to Tq-fold in length: longest first over all heads, so the dispatcher
+    // hands the short blocks to the slots that free up last (with the blocks of one head after
+    // the other, a problem whose blocks are all resident at once left whole compute units with
+    // only long or only short blocks). With a head count that is a multiple of 8 a head stays
+    // on one XCD and its Q blocks share that L2 for K and V.
+    const int n_bh = total_units / Tq;
+    t = Tq - 1 - unit / n_bh;
+    bh = unit % n_bh;
+  } else {
+    // Equal blocks: each XCD walks a contiguous range of units, so the Q blocks of one head
+    // share that XCD's L2 for K and V.
+    if ((total_units & 7) == 0) unit = (blockIdx.x & 7) * (total_units >> 3) + (blockIdx.x >> 3);
+    bh = unit / Tq;
+    t = unit % Tq;
+  }
   const int b = bh / H, h = bh % H;
   const int hk = h / (H / Hkv);
   const int r0 = t * BR;
@@ -227,7 +259,7 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
       const int j = idx >> 3, c8 = idx & 7;
 #pragma unroll
       for (int g = 0; g < C::G; ++g) f_src[u][g] = perm_lds[j * C::G + g] * C::KTROWB + c8 * 16;
-      f_dst[u] = j * C::KTROWB + ((((c8 >> 1) ^ ((j >> 1) & 3)) << 1) | (c8 & 1)) * 16;
+      f_dst[u] = j * C::KTROWB + ((((c8 >> 1) ^ kf_swizzle(j)) << 1) | (c8 & 1)) * 16;
     }
   }
 
@@ -254,7 +286,7 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
     const int slot = (j * C::NW + wave) * 64 + lane;
     const int row = slot / C::CH, pc = slot % C::CH;
     if constexpr (!DISTR) dma_k[j] = row * C::ROWB + (pc ^ (D == 128 ? (row & 15) : ((row >> 1) & 7))) * 16;
-    const int lseg = (pc >> 1) ^ (D == 128 ? (row & 7) : ((row >> 1) & 3));
+    const int lseg = (pc >> 1) ^ v_swizzle<C::ROWB>(row);
     dma_v[j] = row * C::ROWB + (lseg * 2 + (pc & 1)) * 16;
   }
   typedef __attribute__((address_space(3))) void lds_void;
@@ -323,7 +355,7 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf)
         ka_off[mb * 2 + hf] = (8 * hh + 4 * hf + r4) * C::KTROWB +
-                              ((2 * mb + ((lane >> 4) & 1)) ^ ((2 * hf + (r4 >> 1)) & 3)) * 32 + 8 * (lane & 3);
+                              ((2 * mb + ((lane >> 4) & 1)) ^ kf_swizzle(4 * hf + r4)) * 32 + 8 * (lane & 3);
   } else {
 #pragma unroll
     for (int s = 0; s < C::KSTEPS; ++s)
@@ -334,7 +366,7 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   int va_off[D / 32];
   {
     const int row_l = 4 * hh + ((lane & 15) >> 2);
-    const int swz = D == 128 ? (row_l & 7) : ((row_l >> 1) & 3);
+    const int swz = v_swizzle<C::ROWB>(row_l);
 #pragma unroll
     for (int mb = 0; mb < D / 32; ++mb)
       va_off[mb] = row_l * C::ROWB + ((2 * mb + ((lane >> 4) & 1)) ^ swz) * 32 + 8 * (lane & 3);
