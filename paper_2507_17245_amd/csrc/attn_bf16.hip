@@ -187,21 +187,22 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   // Workgroup -> (batch*head, Q block). Consecutive workgroup ids go round-robin over the 8 XCDs.
   int unit = blockIdx.x;
   int bh, t;
-  if (causal) {
-    // Blocks differ up to Tq-fold in length: longest first over all heads, so the dispatcher
-    // hands the short blocks to the slots that free up last (with the blocks of one head after
-    // the other, a problem whose blocks are all resident at once left whole compute units with
-    // only long or only short blocks). With a head count that is a multiple of 8 a head stays
-    // on one XCD and its Q blocks share that L2 for K and V.
+  if (causal == 2) {
+    // Causal blocks differ up to Tq-fold in length. When (nearly) all of them are resident at
+    // once, head after head would leave whole compute units with only long or only short
+    // blocks: take them longest first over all heads, so that every round of the dispatcher
+    // spreads one length class over the chip and the short blocks fill the slots that free up
+    // last. With a head count that is a multiple of 8 a head still stays on one XCD.
     const int n_bh = total_units / Tq;
     t = Tq - 1 - unit / n_bh;
     bh = unit % n_bh;
   } else {
-    // Equal blocks: each XCD walks a contiguous range of units, so the Q blocks of one head
-    // share that XCD's L2 for K and V.
+    // Each XCD walks a contiguous range of units, so the Q blocks of one head run together
+    // and share that XCD's L2 for K and V; the causal blocks of a head longest first.
     if ((total_units & 7) == 0) unit = (blockIdx.x & 7) * (total_units >> 3) + (blockIdx.x >> 3);
     bh = unit / Tq;
     t = unit % Tq;
+    if (causal) t = Tq - 1 - t;
   }
   const int b = bh / H, h = bh % H;
   const int hk = h / (H / Hkv);
@@ -608,9 +609,14 @@ hipError_t launch_one(const void* q, const void* k, const void* v, void* o, cons
   const int Tq = (pb.N + BR - 1) / BR;
   const long long units = (long long)pb.B * pb.H * Tq;
   const float scale_log2e = pb.scale * 1.4426950408889634f;
+  // causal_mode 2 = blocks issued longest first over all heads (see the kernel): for problems
+  // of up to 8 workgroups per compute unit, where load balance matters more than L2 locality
+  // (with more blocks the dispatcher balances by itself and the head-major order fetches half
+  // as many bytes from HBM).
+  const int causal_mode = pb.causal ? (units <= 8 * 256 ? 2 : 1) : 0;
   hipLaunchKernelGGL((attn_bf16_kernel<D, BR, KRED, DISTR>), dim3((unsigned)units), dim3(BR * 2), 0,
                      stream, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, perm, (const f16*)kt,
-                     (pb.N + kBc - 1) / kBc * kBc, pb.H, pb.Hkv, pb.N, Tq, pb.causal, scale_log2e, (int)units);
+                     (pb.N + kBc - 1) / kBc * kBc, pb.H, pb.Hkv, pb.N, Tq, causal_mode, scale_log2e, (int)units);
   return hipGetLastError();
 }
 
