@@ -94,9 +94,8 @@ __device__ inline int v_swizzle(int row) {
 }
 // The fused tile K_f^T (128-byte rows) keeps a swizzle that leaves a two-way conflict on its
 // transposing reads: those reads are limited by the return path, not by the banks (same
-// throughput in a micro-benchmark), and the kernels built with the conflict-free form were
-// measured 2 % (d = 128) to 25 % (d = 64, through a change of register count and residency)
-// slower.
+// throughput in a micro-benchmark), and the kernels built with the conflict-free form (row & 2)
+// were measured within 1 % at d = 128 and 4 % slower at d = 64.
 __device__ inline int kf_swizzle(int row) { return (row >> 1) & 3; }
 
 template <int D, int BR, int KRED, bool DISTR>
@@ -119,16 +118,14 @@ struct Cfg {
   //          32-byte segment' = segment ^ (row & 2)         (D = 64: 4 segments per row, rows of
   //                                                          opposite parity sit in opposite bank halves)
   //    The loading lane fetches the global chunk that belongs at its LDS position.
-  //  * distr path: the keys arrive transposed and in half precision (K^T, one row of 64 keys =
-  //    128 bytes per channel, written once per forward by the key pre-pass). The raw tile is
-  //    loaded unswizzled; the fused tile K_f^T (one 128-byte row per group) is written by the
-  //    waves and read back with transposing accesses, so it uses the V swizzle for 128-byte rows.
+  //  * distr path: the keys arrive transposed and in half precision (K^T in global memory, one
+  //    row of 64 keys = 128 bytes per channel and tile, written once per forward by the key
+  //    pre-pass). Only the fused tile K_f^T (one 128-byte row per group) lives in LDS: written by
+  //    the waves, read back with transposing accesses, segments swizzled by kf_swizzle.
   static constexpr int ROWB = D * 2;              // bytes of an unpadded K / V row
   static constexpr int TILEB = kBc * ROWB;        // bytes of an unpadded 64-row tile
   static constexpr int KTROWB = kBc * 2;          // bytes of a K^T / K_f^T row (64 keys)
   static constexpr int KX_BYTES = DISTR ? KRED * KTROWB : TILEB;   // one Kx buffer: K_f^T or K
-  static constexpr int KT_BYTES = D * KTROWB;     // raw K^T tile (distr)
-  static constexpr int KT_LOADS = D / 8 / NW;     // 1 KB direct loads per wave for a K^T tile
   static constexpr int FUSE_OUT = (KRED * 8 + T - 1) / T;   // 16-byte fused outputs per thread and tile
   static constexpr int KSTEPS = KRED / 16;        // MFMA steps of the score product
 };
@@ -170,9 +167,6 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   __shared__ __attribute__((aligned(1024))) char v_lds1[C::TILEB];
   auto kx_buf = [&](int par) -> char* { return par ? kx_lds1 : kx_lds0; };
   auto v_buf = [&](int par) -> char* { return par ? v_lds1 : v_lds0; };
-  __shared__ __attribute__((aligned(1024))) char kt_lds0[DISTR ? C::KT_BYTES : 16];   // raw K^T tiles
-  __shared__ __attribute__((aligned(1024))) char kt_lds1[DISTR ? C::KT_BYTES : 16];
-  auto kt_buf = [&](int par) -> char* { return par ? kt_lds1 : kt_lds0; };
   // The block's permutation is only needed while the prologue builds the sampled-query operands
   // and the fusion offsets: it borrows the head of the second V buffer, which receives its
   // first tile in the first loop iteration (after the prologue's barriers).
@@ -259,7 +253,8 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
       const int idx = min(tid + u * C::T, KRED * 8 - 1);
       const int j = idx >> 3, c8 = idx & 7;
 #pragma unroll
-      for (int g = 0; g < C::G; ++g) f_src[u][g] = perm_lds[j * C::G + g] * C::KTROWB + c8 * 16;
+      for (int g = 0; g < C::G; ++g)
+        f_src[u][g] = perm_lds[j * C::G + g] * Npad * 2 + c8 * 16;
       f_dst[u] = j * C::KTROWB + ((((c8 >> 1) ^ kf_swizzle(j)) << 1) | (c8 & 1)) * 16;
     }
   }
@@ -302,34 +297,35 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   };
   auto dma_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
-  // distr: raw K^T tile (D channel rows of 64 keys) by direct loads, unswizzled: LDS row =
-  // channel, so 1 KB block number (j*NW + wave) holds 8 channel rows.
+  // distr: K^T of this kv head, [D channel rows][Npad keys] half.
   const __amdgpu_buffer_rsrc_t kt_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       (void*)(DISTR ? kt + (size_t)(b * Hkv + hk) * D * Npad : nullptr), 0, (unsigned)D * Npad * 2, 0x00020000);
-  int dma_kt[DISTR ? C::KT_LOADS : 1];
-  if constexpr (DISTR) {
-#pragma unroll
-    for (int j = 0; j < C::KT_LOADS; ++j) {
-      const int slot = (j * C::NW + wave) * 64 + lane;
-      dma_kt[j] = (slot >> 3) * Npad * 2 + (slot & 7) * 16;
-    }
-  }
-  auto dma_kt_tile = [&](int tile, int buf) {
-    if constexpr (DISTR)
-      dma_blocks(std::integral_constant<int, C::KT_LOADS>(), kt_rsrc, tile * C::KTROWB, dma_kt, kt_buf(buf));
-  };
   // ---- fusion (Sec. 3.2): K_f^T[j][n] = sum over the group's channels c of K^T[c][n], eight keys
-  // at a time with packed half adds. For G* = 2 the sum of two bf16-valued halves is rounded to
-  // half once; larger groups add pairwise.
-  auto fuse = [&](int buf) {   // raw tile in kt_buf(buf) -> K_f^T in kx_buf(buf)
+  // at a time with packed half adds (for G* = 2 the sum of two bf16-valued halves is rounded to
+  // half once; larger groups add one channel after the other). Every thread loads the 16-byte
+  // pieces it sums straight from K^T in global memory (8 lanes cover one 128-byte channel row)
+  // one tile iteration before it adds them, so the LDS only sees K_f^T (8-16 KB per tile): with
+  // the raw tile staged in LDS and summed from there (direct load, 16 KB read, K_f^T written)
+  // the kernel was bound by LDS traffic and 2-12 % slower.
+    typedef f16x8 Pieces[DISTR ? C::FUSE_OUT : 1][DISTR ? C::G : 1];
+  Pieces piece;   // the set the main loop carries from one iteration to the next
+  auto load_pieces = [&](int tile, Pieces& pc) {
+    if constexpr (DISTR) {
+#pragma unroll
+      for (int u = 0; u < C::FUSE_OUT; ++u)
+#pragma unroll
+        for (int g = 0; g < C::G; ++g)
+          pc[u][g] = __builtin_bit_cast(f16x8, __builtin_amdgcn_raw_buffer_load_b128(kt_rsrc, f_src[u][g], tile * C::KTROWB, 0));
+    }
+  };
+  auto fuse_pieces = [&](int buf, const Pieces& pc) {   // loaded pieces -> K_f^T in kx_buf(buf)
     if constexpr (DISTR) {
       char* dst = kx_buf(buf);
-      const char* src = kt_buf(buf);
 #pragma unroll
       for (int u = 0; u < C::FUSE_OUT; ++u) {
-        f16x8 acc = *(const f16x8*)(src + f_src[u][0]);
+        f16x8 acc = pc[u][0];
 #pragma unroll
-        for (int g = 1; g < C::G; ++g) acc += *(const f16x8*)(src + f_src[u][g]);
+        for (int g = 1; g < C::G; ++g) acc += pc[u][g];
         if (KRED * 8 % C::T == 0 || tid + u * C::T < KRED * 8) *(f16x8*)(dst + f_dst[u]) = acc;
       }
     }
@@ -449,8 +445,8 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
       // K^T(it+2), loaded during the previous iteration, is fused now into the buffer K_f^T(it)
       // has left. Nothing in this iteration depends on the fusion: it runs beside the MFMAs.
       if constexpr (DISTR) {
-        dma_kt_tile(it + 3, par ^ 1);
-        fuse(par);
+        fuse_pieces(par, piece);       // K^T(it+2), loaded during the previous iteration
+        load_pieces(it + 3, piece);
       }
 #endif
       if constexpr (!DISTR) dma_tile(k_rsrc, it + 2, dma_k, kx_buf(par));
@@ -547,14 +543,14 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   // ---- prologue: tiles 0 (K, V) and 1 (K) into LDS, scores of tile 0 ---------------------------
   dma_tile(v_rsrc, 0, dma_v, v_lds0);
   if constexpr (DISTR) {
-    dma_kt_tile(0, 0);
-    dma_kt_tile(1, 1);
-    dma_wait();
-    __syncthreads();
-    fuse(0);
-    fuse(1);
-    __syncthreads();   // raw tiles 0 and 1 are consumed, K_f^T(0) and K_f^T(1) are visible
-    dma_kt_tile(2, 0);   // lands while the scores of tile 0 are computed
+    Pieces first;        // tiles 0 and 1 travel together (registers are plentiful before the loop)
+    load_pieces(0, first);
+    load_pieces(1, piece);
+    fuse_pieces(0, first);
+    fuse_pieces(1, piece);
+    load_pieces(2, piece);
+    dma_wait();          // V(0) has landed (and, with it, the pieces of tile 2)
+    __syncthreads();     // K_f^T(0), K_f^T(1) and V(0) are visible
   } else {
     dma_tile(k_rsrc, 0, dma_k, kx_lds0);
     if (n_tiles > 1) dma_tile(k_rsrc, 1, dma_k, kx_lds1);
@@ -568,8 +564,7 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   qk(0, s0);
   move_reference(row_max(yes, 0, s0));
   if constexpr (DISTR) {
-    dma_wait();
-    __syncthreads();   // raw K^T(2) is in; K_f^T(0) may be rewritten by the first iteration's fusion
+    __syncthreads();   // K_f^T(0) may be rewritten by the first iteration's fusion
   }
 
   // Tile it+1 needs no mask while it+1 < n_full. The main loop is unrolled by two so that the
