@@ -243,8 +243,9 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
 
   // ---- fusion bookkeeping, fixed for the Q block ------------------------------------------------
   // Fused output u of this thread is the 16-byte piece (8 keys) number idx % 8 of group
-  // idx / 8, idx = tid + u*T: it sums the same piece of the group's G channel rows of the raw
-  // K^T tile and lands in row idx / 8 of K_f^T at the swizzled position.
+  // idx / 8, idx = tid + u*T: it sums the same piece of the group's G channel rows of K^T
+  // (f_src: byte offset of the piece inside the head's K^T, tile 0) and lands in row idx / 8 of
+  // K_f^T at the swizzled position (f_dst).
   int f_src[DISTR ? C::FUSE_OUT : 1][DISTR ? C::G : 1];
   int f_dst[DISTR ? C::FUSE_OUT : 1];
   if constexpr (DISTR) {
@@ -441,9 +442,9 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
     // has left (barrier): K(it+2) replaces K(it), V(it+1) replaces V(it-1).
     if constexpr (HAS_NEXT) {
 #ifndef DA_ABL_NOFUSE
-      // distr: raw K^T(it+3) replaces raw K^T(it+1), fused in the previous iteration; raw
-      // K^T(it+2), loaded during the previous iteration, is fused now into the buffer K_f^T(it)
-      // has left. Nothing in this iteration depends on the fusion: it runs beside the MFMAs.
+      // distr: the pieces of K^T(it+2), loaded during the previous iteration, are summed now
+      // into the buffer K_f^T(it) has left, and the loads of K^T(it+3) take their registers.
+      // Nothing in this iteration depends on the fusion: it runs beside the MFMAs.
       if constexpr (DISTR) {
         fuse_pieces(par, piece);       // K^T(it+2), loaded during the previous iteration
         load_pieces(it + 3, piece);
