@@ -90,9 +90,13 @@ def main():
         p_lsh = da.make_params(q, k, v, n_groups=n_groups, perm_out=perm, **common)
         p_ex = da.make_params(q, k, v, **common)
         step = lambda: da.distr_attn_fwd_ex(q, k, v, o, p_full)
+        tw = time.perf_counter()
         for _ in range(warmup):
             step()
         torch.cuda.synchronize()
+        while time.perf_counter() - tw < 0.05:   # short workloads: keep warming until the clocks have ramped up
+            step()
+            torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
             step()
