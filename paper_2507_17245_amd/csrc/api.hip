@@ -158,8 +158,13 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
     uint8_t* table = nullptr;
     rc = get_scratch(p, r, p->perm_in == nullptr, &table, &kt);
     if (rc) return rc;
+    // bf16 path, up to 16 projections, no table asked for: the attention kernel hashes and groups
+    // its own Q block in its prologue (same arithmetic as the LSH kernel) and no table is written.
+    const bool lsh_in_kernel = r.dtype == DA_BF16 && !p->perm_in && !p->perm_out && !p->hash_out && r.pb.n_planes <= 16;
     if (p->perm_in) {
       perm = p->perm_in;
+    } else if (lsh_in_kernel) {
+      perm = nullptr;
     } else {
       rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, table, p->hash_out, r.stream), "lsh_group launch");
       if (rc) return rc;

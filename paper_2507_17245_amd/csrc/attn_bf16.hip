@@ -155,7 +155,8 @@ template <int D, int BR, int KRED, bool DISTR>
 __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     bf16* __restrict__ o, const uint8_t* __restrict__ perm, const f16* __restrict__ kt, int Npad,
-    int H, int Hkv, int N, int Tq, int causal, float scale_log2e, int total_units) {
+    int H, int Hkv, int N, int Tq, int causal, float scale_log2e, int total_units, int n_planes,
+    int gray_mode, uint64_t lsh_seed) {
   using C = Cfg<D, BR, KRED, DISTR>;
   using kx8 = typename std::conditional<DISTR, f16x8, bf16x8>::type;
   // Kx and V tiles are double-buffered: while tile i multiplies, tile i+1 (V) / i+2 (K) lands.
@@ -211,8 +212,61 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   const int q_ld = min(q_abs, N - 1);          // ragged block: load a valid row, never store it
 
   if constexpr (DISTR) {
-    const size_t pbase = ((size_t)bh * Tq + t) * D;
-    for (int i = tid; i < D; i += C::T) perm_lds[i] = perm[pbase + i];
+    if (perm != nullptr) {
+      const size_t pbase = ((size_t)bh * Tq + t) * D;
+      for (int i = tid; i < D; i += C::T) perm_lds[i] = perm[pbase + i];
+    } else {
+      // ---- LSH hash-and-group of this Q block inside the workgroup (Sec. 3.2, 3.3) -------------
+      // Same arithmetic as the stand-alone LSH kernel (float, one fused multiply-add per row,
+      // rows ascending, from +0), so the table equals that kernel's bit for bit; here it costs
+      // no launch, no table in HBM, and runs while the CU's other workgroup keeps the matrix
+      // pipes busy. Up to 16 projections: R[row][16] borrows the first V buffer (8 KB), the
+      // codes and hashes borrow the first Kx buffer; both are filled only after the barriers below.
+      constexpr int NPG = C::T / D;             // threads per channel
+      constexpr int PPT = 16 / NPG;             // projections per thread: pg*PPT .. pg*PPT+PPT-1
+      static_assert(C::T % D == 0 && BR * 16 * 4 <= C::TILEB && 2 * D * 4 <= C::KX_BYTES, "LSH scratch fits");
+      float* R_lds = (float*)v_lds0;
+      uint32_t* code_lds = (uint32_t*)kx_lds0;
+      uint32_t* hash_lds = code_lds + D;
+      for (int i = tid; i < BR * 16; i += C::T)
+        R_lds[i] = (i & 15) < n_planes ? hyperplane_entry(lsh_seed, (uint32_t)(i & 15), (uint32_t)(i >> 4)) : 0.0f;
+      if (tid < D) code_lds[tid] = 0;
+      __syncthreads();
+      const int c = tid % D, pg = tid / D;
+      const int rows = min(BR, N - r0);
+      const bf16* qcol = qh + (size_t)r0 * D + c;
+      float acc[PPT];
+#pragma unroll
+      for (int j = 0; j < PPT; ++j) acc[j] = 0.0f;
+      // 16 column loads in flight per thread: with two workgroups per CU nothing else hides
+      // their latency here (the stand-alone kernel, at 8 workgroups per CU, does with 4).
+#pragma unroll 16
+      for (int r = 0; r < rows; ++r) {
+        const float x = (float)qcol[(size_t)r * D];
+#pragma unroll
+        for (int j = 0; j < PPT; ++j) acc[j] = __builtin_fmaf(x, R_lds[r * 16 + pg * PPT + j], acc[j]);
+      }
+      uint32_t bits = 0;
+#pragma unroll
+      for (int j = 0; j < PPT; ++j) {
+        const int pl = pg * PPT + j;
+        if (pl < n_planes && acc[j] > 0.0f) bits |= 1u << (n_planes - 1 - pl);   // projection 0 = top bit
+      }
+      if (NPG == 1) code_lds[c] = bits;
+      else if (bits) atomicOr(&code_lds[c], bits);
+      __syncthreads();
+      if (tid < D) hash_lds[tid] = lsh_hash_of_code(code_lds[tid], gray_mode);
+      __syncthreads();
+      if (tid < D) {   // rank by counting = stable ascending sort; perm = inverse of the rank
+        const uint32_t mine = hash_lds[tid];
+        int rank = 0;
+        for (int o = 0; o < D; ++o) {
+          const uint32_t other = hash_lds[o];
+          rank += (other < mine || (other == mine && o < tid)) ? 1 : 0;
+        }
+        perm_lds[rank] = (uint8_t)tid;
+      }
+    }
     __syncthreads();
   }
 
@@ -612,7 +666,8 @@ hipError_t launch_one(const void* q, const void* k, const void* v, void* o, cons
   const int causal_mode = pb.causal ? (units <= 8 * 256 ? 2 : 1) : 0;
   hipLaunchKernelGGL((attn_bf16_kernel<D, BR, KRED, DISTR>), dim3((unsigned)units), dim3(BR * 2), 0,
                      stream, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, perm, (const f16*)kt,
-                     (pb.N + kBc - 1) / kBc * kBc, pb.H, pb.Hkv, pb.N, Tq, causal_mode, scale_log2e, (int)units);
+                     (pb.N + kBc - 1) / kBc * kBc, pb.H, pb.Hkv, pb.N, Tq, causal_mode, scale_log2e, (int)units,
+                     pb.n_planes, pb.gray_mode, pb.seed);
   return hipGetLastError();
 }
 

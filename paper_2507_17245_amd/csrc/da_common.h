@@ -31,6 +31,16 @@ __host__ __device__ inline float hyperplane_entry(uint64_t seed, uint32_t p, uin
   return (float)(sum - 131070) * (1.0f / 65536.0f);
 }
 
+// Hash of a channel from the sign word of its projections (Sec. 3.2). gray_mode 1: the Gray code
+// of the sign word (literal table lookup); otherwise the position of the sign word in the Gray
+// sequence, so that hashes differing by one belong to sign words differing in one projection.
+__host__ __device__ inline uint32_t lsh_hash_of_code(uint32_t code, int gray_mode) {
+  if (gray_mode == 1) return code ^ (code >> 1);
+  uint32_t h = code;
+  h ^= h >> 1; h ^= h >> 2; h ^= h >> 4; h ^= h >> 8; h ^= h >> 16;
+  return h;
+}
+
 struct Problem {
   int B, H, Hkv, N, d, Br, n_groups, causal, n_planes, gray_mode;
   uint64_t seed;

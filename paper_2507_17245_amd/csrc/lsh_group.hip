@@ -85,14 +85,7 @@ __global__ __launch_bounds__(kLshThreads) void lsh_group_kernel(
   __syncthreads();
 
   if (tid < D) {
-    uint32_t code = code_lds[tid];
-    uint32_t h;
-    if (gray_mode == 1) {
-      h = code ^ (code >> 1);  // Gray code of the sign word
-    } else {                   // position of the sign word in the Gray sequence
-      h = code;
-      h ^= h >> 1; h ^= h >> 2; h ^= h >> 4; h ^= h >> 8; h ^= h >> 16;
-    }
+    const uint32_t h = lsh_hash_of_code(code_lds[tid], gray_mode);
     hash_lds[tid] = h;
   }
   __syncthreads();

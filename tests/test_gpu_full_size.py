@@ -52,7 +52,11 @@ def test_full_size_parity(name, n_groups):
     mx, mean = U.assert_close(got[valid], ref[valid], cfg.dtype, "distr")
     print(f"  distr: max-abs {mx:.3g} mean-abs {mean:.3g}", flush=True)
     assert np.isfinite(o_gpu).all()
-    del o_gpu
+    # the call bench.py times asks for no tables: the attention kernel then does the LSH stage of
+    # its own Q block, and must give the same output bit for bit
+    o_self, _, _ = U.run_gpu(cfg, q, k, v, distr=True, want_tables=False)
+    assert np.array_equal(o_self, o_gpu), "in-kernel LSH and LSH kernel disagree"
+    del o_gpu, o_self
     o_ex, _, _ = U.run_gpu(cfg, q, k, v, distr=False)
     ref_ex = oracle.exact_fwd_tiles(q, k, v, p, tiles)
     mx, mean = U.assert_close(gather(o_ex)[valid], ref_ex[valid], cfg.dtype, "exact")

@@ -53,6 +53,10 @@ def test_small_cases_match_oracle(cfg):
     assert np.array_equal(hash_gpu, hash_ref), "hashes differ"
     assert np.array_equal(perm_gpu, perm_ref), "permutations differ"
     U.assert_close(o_gpu, oracle.distr_fwd(q, k, v, p), cfg.dtype, "distr")
+    # without table outputs the bf16 attention kernel hashes and groups its Q block itself:
+    # same tables, so the same output bit for bit
+    o_self, _, _ = U.run_gpu(cfg, q, k, v, distr=True, want_tables=False)
+    assert np.array_equal(o_self, o_gpu), "in-kernel LSH and LSH kernel disagree"
     o_ex, _, _ = U.run_gpu(cfg, q, k, v, distr=False)
     U.assert_close(o_ex, oracle.exact_fwd(q, k, v, p), cfg.dtype, "exact")
 
@@ -85,6 +89,14 @@ def test_gray_modes_seeds_and_plane_counts():
                 hash_ref, perm_ref, _ = oracle.lsh_group(q, U.oracle_params(c, gray_mode=gray_mode))
                 assert np.array_equal(hash_gpu, hash_ref), (gray_mode, planes, seed)
                 assert np.array_equal(perm_gpu, perm_ref), (gray_mode, planes, seed)
+    # the attention kernel's own LSH stage (no table outputs, up to 16 projections) follows the
+    # same options: its output equals the output computed from the LSH kernel's table
+    _, k, v = W.make(cfg)
+    for gray_mode, planes, seed in ((0, 1, 0), (1, 4, 3), (0, 7, 12345678901234567), (1, 16, 5), (0, 31, 1)):
+        c = cfg.scaled(n_planes=planes, lsh_seed=seed)
+        o_tab, _, _ = U.run_gpu(c, q, k, v, distr=True, want_tables=True, gray_mode=gray_mode)
+        o_self, _, _ = U.run_gpu(c, q, k, v, distr=True, want_tables=False, gray_mode=gray_mode)
+        assert np.array_equal(o_tab, o_self), (gray_mode, planes, seed)
 
 
 def test_degenerate_inputs():
