@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the DistrAttention forward pass on one MI355X.
 
-A step is one pass of the whole hot path -- LSH hash-and-group kernel, key pre-pass, then the
-attention kernel with in-LDS key fusion -- over one batch of synthetic input already resident in HBM.
+A step is one pass of the whole hot path -- key pre-pass, then the attention kernel, which hashes
+and groups each query block in its prologue and fuses the keys tile by tile (float path: LSH
+kernel, then attention kernel) -- over one batch of synthetic input already resident in HBM.
 The headline workload is the long-sequence configuration (the largest one of the five); the
 other configurations are measured in the same run and reported inside the same JSON line
 under "configs". The exact-attention kernel, built the same way, is timed beside it.

@@ -102,3 +102,20 @@ def test_workspace_bytes():
     need = da.distr_attn_workspace_bytes(p)
     assert need >= 2 * 4 * 4 * 64 and need % 256 == 0
     assert da.distr_attn_workspace_bytes(_params(n_groups=7)) == 0
+
+
+def test_bench_refuses_more_than_one_gpu_and_reads_its_traffic_figure():
+    """Host logic of bench.py that needs no GPU: the one-GPU rule and the profile line it quotes."""
+    import json
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                         capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in (res.stdout + res.stderr)
+    with open(os.path.join(root, "profiles", "attn_bf16_long_hbm_traffic.md")) as f:
+        lines = [l for l in f if l.startswith("bench-traffic:")]
+    assert len(lines) == 1
+    rec = json.loads(lines[0].split(":", 1)[1])
+    assert rec["workload"] == "long" and rec["hbm_bytes_per_launch"] > 5e8
