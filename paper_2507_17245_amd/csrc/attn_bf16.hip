@@ -618,9 +618,9 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   f32x16 s0[2], s1[2];
   qk(0, s0);
   move_reference(row_max(yes, 0, s0));
-  if constexpr (DISTR) {
-    __syncthreads();   // K_f^T(0) may be rewritten by the first iteration's fusion
-  }
+  // The first iteration refills the buffer of tile 0 (direct load of K(2), or the fusion of
+  // K_f^T(2)): every wave must have read its scores of tile 0 out of it first.
+  __syncthreads();
 
   // Tile it+1 needs no mask while it+1 < n_full. The main loop is unrolled by two so that the
   // two score register sets swap roles without copies.

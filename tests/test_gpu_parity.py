@@ -34,6 +34,9 @@ SMALL_CASES = [
     small("vit", B=1, H=2, Hkv=2, N=200, n_groups=16, Br=128),       # d 64, Br 128, G* = 4
     small("long", H=2, Hkv=2, N=200, Br=64, n_groups=16),            # d 128, Br 64, G* = 8
     small("long", H=2, Hkv=1, N=200, Br=64, n_groups=32, causal=False),
+    small("vit", B=8, N=700, causal=True),                           # 1056 short causal blocks of 1..11 tiles (more
+                                                                     # blocks than the chip holds at once; blocks of 2-3
+                                                                     # tiles once exposed a missing barrier after tile 0)
     small("tiny"),                                                   # float path, full config
     small("tiny", N=150, d=128, n_groups=32, Br=128, causal=True, recipe="normal"),
     small("tiny", N=100, n_groups=1, recipe="normal"),               # float path, one group of all channels
