@@ -14,15 +14,17 @@
 // contraction index kv is enumerated in the accumulator's order on both operands.
 //   exact:  Kx = K tile,  Qx = Q,    contraction over d channels
 //   distr:  Kx = K_f tile (Sec. 3.2 fusion: sum of the group's K channels, built once per
-//           (Q block, K tile) in LDS by all waves together from a transposed half-precision
-//           copy of K, as whole-row packed adds), Qx = Q_r (sampling: the group's first channel
-//           in sorted order, gathered once per Q block), contraction over n_groups = d / G*,
-//           on the f16 matrix path.
+//           (Q block, K tile) by all waves together: packed half adds in registers on pieces of
+//           a transposed half-precision copy of K, result in LDS), Qx = Q_r (sampling: the
+//           group's first channel in sorted order, gathered once per Q block), contraction over
+//           n_groups = d / G*, on the f16 matrix path. The grouping itself (Sec. 3.2 LSH, sort,
+//           groups) is either read from a table or computed by the workgroup in its prologue.
 // Online softmax (reference max, row sum, rescaled accumulator) follows the block-wise scheme of
 // Sec. 2.2.2 in the exp2 domain.
 //
-// Pipeline (one barrier per tile): tiles reach LDS by direct global->LDS loads two tiles (K) /
-// one tile (V) ahead; while the vector ALUs exponentiate tile i the matrix pipe computes the
+// Pipeline (one barrier per tile): K (exact) and V tiles reach LDS by direct global->LDS loads
+// two tiles (K) / one tile (V) ahead, the K^T pieces of the fusion reach registers one tile
+// ahead of their use; while the vector ALUs exponentiate tile i the matrix pipe computes the
 // scores of tile i+1; P.V of tile i runs beside the row maximum of tile i+1.
 #include <type_traits>
 
