@@ -39,8 +39,9 @@ typedef enum { DA_BF16 = 0, DA_F32 = 1 } da_dtype;
 /*
  * Full parameter block (host memory).
  *
- * Supported by the kernels: d in {64, 128}; Br in {64, 128}; Bc = 64; n_groups a multiple
- * of 16 for bf16 (the MFMA contraction step) and any divisor of d for float; 1 <= n_planes <= 32;
+ * Supported by the kernels: d in {64, 128}; Br in {64, 128}; Bc = 64; for bf16 n_groups in
+ * {4, 8, 16, 32, 64, 128} with G* = d / n_groups <= 16 (4 and 8 zero-pad the contraction to one MFMA
+ * step of 16), for float any divisor of d; 1 <= n_planes <= 32;
  * N >= 1 arbitrary (ragged last blocks are masked), N * d * 4 < 2^31; at most 2^31 - 1 query blocks.
  * bf16 DistrAttention path: |q| and |k| beyond 65504 / G* are clamped (the reduced product runs in
  * half precision).

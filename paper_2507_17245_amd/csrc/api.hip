@@ -139,7 +139,7 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
   rc = check_tensors(q, k, v, o);
   if (rc) return rc;
   if (r.dtype == DA_BF16 && !da::attn_bf16_supported(r.pb, distr ? 1 : 0))
-    return fail(DA_ERR_UNSUPPORTED, "bf16 kernels need n_groups in {16, 32, 64, 128} (a multiple of the MFMA step); "
+    return fail(DA_ERR_UNSUPPORTED, "bf16 kernels need n_groups in {4, 8, 16, 32, 64, 128} and groups of at most 16 channels; "
                 "got d=%d Br=%d n_groups=%d", p->d, p->Br, p->n_groups);
   const uint8_t* perm = nullptr;
   void* kt = nullptr;

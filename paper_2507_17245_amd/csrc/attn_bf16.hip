@@ -100,11 +100,13 @@ __device__ inline int v_swizzle(int row) {
 // were measured within 1 % at d = 128 and 4 % slower at d = 64.
 __device__ inline int kf_swizzle(int row) { return (row >> 1) & 3; }
 
-template <int D, int BR, int KRED, bool DISTR>
+// KRED: contraction length of the score product (a multiple of the MFMA step, 16). NG: number of
+// channel groups; smaller than KRED only for n_groups 4 and 8, whose operands are zero-padded to 16.
+template <int D, int BR, int KRED, bool DISTR, int NG = KRED>
 struct Cfg {
   static constexpr int NW = BR / 32;              // wavefronts per workgroup
   static constexpr int T = NW * 64;               // threads
-  static constexpr int G = D / KRED;              // channels per group
+  static constexpr int G = D / NG;                // channels per group
   static constexpr int CH = D / 8;                // 16-byte chunks per row
   static constexpr int CPT = kBc * CH / T;        // chunks each thread stages per tile
   // LDS layouts.
@@ -128,7 +130,7 @@ struct Cfg {
   static constexpr int TILEB = kBc * ROWB;        // bytes of an unpadded 64-row tile
   static constexpr int KTROWB = kBc * 2;          // bytes of a K^T / K_f^T row (64 keys)
   static constexpr int KX_BYTES = DISTR ? KRED * KTROWB : TILEB;   // one Kx buffer: K_f^T or K
-  static constexpr int FUSE_OUT = (KRED * 8 + T - 1) / T;   // 16-byte fused outputs per thread and tile
+  static constexpr int FUSE_OUT = (NG * 8 + T - 1) / T;     // 16-byte fused outputs per thread and tile
   static constexpr int KSTEPS = KRED / 16;        // MFMA steps of the score product
 };
 
@@ -153,13 +155,13 @@ struct Cfg {
 // (one multiply per accumulator register) is skipped for almost every tile.
 constexpr float kTau = 8.0f;
 
-template <int D, int BR, int KRED, bool DISTR>
+template <int D, int BR, int KRED, bool DISTR, int NG>
 __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     bf16* __restrict__ o, const uint8_t* __restrict__ perm, const f16* __restrict__ kt, int Npad,
     int H, int Hkv, int N, int Tq, int causal, float scale_log2e, int total_units, int n_planes,
     int gray_mode, uint64_t lsh_seed) {
-  using C = Cfg<D, BR, KRED, DISTR>;
+  using C = Cfg<D, BR, KRED, DISTR, NG>;
   using kx8 = typename std::conditional<DISTR, f16x8, bf16x8>::type;
   // Kx and V tiles are double-buffered: while tile i multiplies, tile i+1 (V) / i+2 (K) lands.
   // Each buffer is a separate LDS object: the compiler can then tell that the operand reads of
@@ -214,6 +216,17 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   const int q_ld = min(q_abs, N - 1);          // ragged block: load a valid row, never store it
 
   if constexpr (DISTR) {
+    if constexpr (NG < KRED) {
+      // Rows NG..KRED-1 of K_f^T pad the contraction: zeroed once, the fusion never writes them.
+      // (They lie behind the 2*D*4 bytes the LSH stage below borrows from the first buffer:
+      // 2*D*4 <= NG*128 because a group has at most 16 channels.)
+      static_assert(2 * D * 4 <= NG * C::KTROWB, "padding rows and LSH scratch are disjoint");
+      const f16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+      for (int i = NG * C::KTROWB / 16 + tid; i < C::KX_BYTES / 16; i += C::T) {
+        ((f16x8*)kx_lds0)[i] = zero;
+        ((f16x8*)kx_lds1)[i] = zero;
+      }
+    }
     if (perm != nullptr) {
       const size_t pbase = ((size_t)bh * Tq + t) * D;
       for (int i = tid; i < D; i += C::T) perm_lds[i] = perm[pbase + i];
@@ -284,7 +297,10 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
     for (int s = 0; s < C::KSTEPS; ++s) {
 #pragma unroll
       for (int j = 0; j < 8; ++j)
-        qop[s][j] = to_half_sat((float)qrow[perm_lds[(16 * s + 8 * hh + j) * C::G]]);
+        if (NG == KRED || 16 * s + 8 * hh + j < NG)
+          qop[s][j] = to_half_sat((float)qrow[perm_lds[(16 * s + 8 * hh + j) * C::G]]);
+        else
+          qop[s][j] = (f16)0.0f;   // padding of the contraction: no group there
     }
   } else {
 #pragma unroll
@@ -307,7 +323,7 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   if constexpr (DISTR) {
 #pragma unroll
     for (int u = 0; u < C::FUSE_OUT; ++u) {
-      const int idx = min(tid + u * C::T, KRED * 8 - 1);
+      const int idx = min(tid + u * C::T, NG * 8 - 1);
       const int j = idx >> 3, c8 = idx & 7;
 #pragma unroll
       for (int g = 0; g < C::G; ++g)
@@ -383,7 +399,7 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
         f16x8 acc = pc[u][0];
 #pragma unroll
         for (int g = 1; g < C::G; ++g) acc += pc[u][g];
-        if (KRED * 8 % C::T == 0 || tid + u * C::T < KRED * 8) *(f16x8*)(dst + f_dst[u]) = acc;
+        if (NG * 8 % C::T == 0 || tid + u * C::T < NG * 8) *(f16x8*)(dst + f_dst[u]) = acc;
       }
     }
   };
@@ -655,7 +671,7 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   }
 }
 
-template <int D, int BR, int KRED, bool DISTR>
+template <int D, int BR, int KRED, bool DISTR, int NG = KRED>
 hipError_t launch_one(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
                       const void* kt, const Problem& pb, hipStream_t stream) {
   const int Tq = (pb.N + BR - 1) / BR;
@@ -666,7 +682,7 @@ hipError_t launch_one(const void* q, const void* k, const void* v, void* o, cons
   // (with more blocks the dispatcher balances by itself and the head-major order fetches half
   // as many bytes from HBM).
   const int causal_mode = pb.causal ? (units <= 8 * 256 ? 2 : 1) : 0;
-  hipLaunchKernelGGL((attn_bf16_kernel<D, BR, KRED, DISTR>), dim3((unsigned)units), dim3(BR * 2), 0,
+  hipLaunchKernelGGL((attn_bf16_kernel<D, BR, KRED, DISTR, NG>), dim3((unsigned)units), dim3(BR * 2), 0,
                      stream, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, perm, (const f16*)kt,
                      (pb.N + kBc - 1) / kBc * kBc, pb.H, pb.Hkv, pb.N, Tq, causal_mode, scale_log2e, (int)units,
                      pb.n_planes, pb.gray_mode, pb.seed);
@@ -677,12 +693,15 @@ template <int D, int BR>
 hipError_t dispatch_kred(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
                          const void* kt, const Problem& pb, int distr, hipStream_t stream) {
   if (!distr) return launch_one<D, BR, D, false>(q, k, v, o, perm, kt, pb, stream);
-  switch (pb.n_groups) {
+  switch (pb.n_groups) {   // n_groups = d (groups of one channel) is the exact product: dispatched by the caller
+    case 4:                // fewer groups than one MFMA step: contraction zero-padded to 16
+      if constexpr (D == 64) return launch_one<D, BR, 16, true, 4>(q, k, v, o, perm, kt, pb, stream);
+      return hipErrorInvalidValue;
+    case 8: return launch_one<D, BR, 16, true, 8>(q, k, v, o, perm, kt, pb, stream);
     case 16: return launch_one<D, BR, 16, true>(q, k, v, o, perm, kt, pb, stream);
     case 32: return launch_one<D, BR, 32, true>(q, k, v, o, perm, kt, pb, stream);
-    case 64: return launch_one<D, BR, 64, true>(q, k, v, o, perm, kt, pb, stream);
-    case 128:
-      if constexpr (D == 128) return launch_one<D, BR, 128, true>(q, k, v, o, perm, kt, pb, stream);
+    case 64:
+      if constexpr (D == 128) return launch_one<D, BR, 64, true>(q, k, v, o, perm, kt, pb, stream);
       [[fallthrough]];
     default: return hipErrorInvalidValue;
   }
@@ -694,9 +713,9 @@ bool attn_bf16_supported(const Problem& pb, int distr) {
   if (pb.d != 64 && pb.d != 128) return false;
   if (pb.Br != 64 && pb.Br != 128) return false;
   if (distr) {
-    const int kr = pb.n_groups;
-    if (kr != 16 && kr != 32 && kr != 64 && kr != 128) return false;
-    if (kr > pb.d || pb.d % kr != 0) return false;
+    const int kr = pb.n_groups;   // groups of up to 16 channels (G* in {1, 2, 4, 8, 16}, Sec. 3.2 and Table 4)
+    if (kr != 4 && kr != 8 && kr != 16 && kr != 32 && kr != 64 && kr != 128) return false;
+    if (kr > pb.d || pb.d % kr != 0 || pb.d / kr > 16) return false;
   }
   return true;
 }

@@ -34,6 +34,10 @@ SMALL_CASES = [
     small("vit", B=1, H=2, Hkv=2, N=200, n_groups=16, Br=128),       # d 64, Br 128, G* = 4
     small("long", H=2, Hkv=2, N=200, Br=64, n_groups=16),            # d 128, Br 64, G* = 8
     small("long", H=2, Hkv=1, N=200, Br=64, n_groups=32, causal=False),
+    small("mid", B=1, H=2, Hkv=2, N=300, n_groups=8),                # G* = 16: contraction zero-padded to one MFMA step
+    small("vit", B=1, H=2, Hkv=1, N=200, n_groups=8, Br=128, causal=True),   # d 64, G* = 8
+    small("vit", B=1, H=2, Hkv=2, N=130, n_groups=4),                # d 64, G* = 16, Br 64
+    small("long", H=2, Hkv=2, N=200, Br=64, n_groups=8),             # d 128, Br 64, G* = 16
     small("vit", B=8, N=700, causal=True),                           # 1056 short causal blocks of 1..11 tiles (more
                                                                      # blocks than the chip holds at once; blocks of 2-3
                                                                      # tiles once exposed a missing barrier after tile 0)

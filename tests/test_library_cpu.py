@@ -71,7 +71,8 @@ FAKE_O = ctypes.c_void_p(0x2000)
     (dict(Br=32), da.DA_ERR_UNSUPPORTED),
     (dict(Bc=128), da.DA_ERR_UNSUPPORTED),
     (dict(n_planes=33), da.DA_ERR_UNSUPPORTED),
-    (dict(n_groups=8), da.DA_ERR_UNSUPPORTED),            # below the MFMA contraction step
+    (dict(n_groups=2), da.DA_ERR_UNSUPPORTED),            # groups of 32 channels: more than the bf16 kernels take
+    (dict(d=128, n_groups=4), da.DA_ERR_UNSUPPORTED),
     (dict(N=1 << 23, d=128, n_groups=64), da.DA_ERR_UNSUPPORTED),   # a head of 4 GiB: 32-bit tile offsets
 ])
 def test_bad_arguments_fail_on_the_host(kw, code):
