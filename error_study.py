@@ -67,7 +67,8 @@ def gpu_study():
         ref = o_ex.float()
         rms = float(ref.pow(2).mean().sqrt())
         ident = torch.arange(cfg.d, dtype=torch.uint8, device="cuda").expand(cfg.B, cfg.H, cfg.Tq, cfg.d).contiguous()
-        groups = [g for g in (W.MID_GROUP_SWEEP if name == "mid" else (cfg.n_groups,)) if g < cfg.d]
+        # "mid": every group size of the paper's Table 4 (G* = 2, 4, 8, 16)
+        groups = (64, 32, 16, 8) if name == "mid" else (cfg.n_groups,)
         for ng in groups:
             cells = []
             for kw in (dict(gray_mode=0), dict(gray_mode=1), dict(perm_in=ident)):
