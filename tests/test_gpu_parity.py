@@ -215,3 +215,38 @@ def test_side_stream_and_back_to_back_calls():
     side.synchronize()
     for i, o in enumerate(outs):
         assert np.array_equal(o.float().cpu().numpy().astype(np.float64), expect[i % 2])
+
+
+def test_forward_replays_from_a_hip_graph():
+    """With a caller-provided workspace a forward is launches only (no allocation, no host
+    synchronisation, no memset), so it can be captured once and replayed: every replay, with the
+    program's own eager work and synchronisations in between, must equal the eager result on the
+    inputs of that moment."""
+    import torch
+    import paper_2507_17245_amd as da
+    U = _util()
+    for cfg in (small("mid", B=1, H=2, Hkv=2, N=300, n_groups=64), small("llama", H=8, Hkv=2, N=333)):
+        q, k, v = W.make(cfg)
+        tq, tk, tv = (U.to_dev(x, "bf16") for x in (q, k, v))
+        o_graph, o_eager = torch.empty_like(tq), torch.empty_like(tq)
+        common = dict(Br=cfg.Br, n_groups=cfg.n_groups, causal=cfg.causal, lsh_seed=cfg.lsh_seed)
+        ws_bytes = da.distr_attn_workspace_bytes(da.make_params(tq, tk, tv, **common))
+        ws_graph = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        ws_eager = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(graph, stream=side):
+            da.distr_attn_fwd_ex(tq, tk, tv, o_graph, da.make_params(tq, tk, tv, workspace=ws_graph, **common))
+        torch.cuda.synchronize()
+        gen = torch.Generator(device="cuda").manual_seed(5)
+        for rep in range(4):
+            if rep:   # new inputs in the captured buffers
+                for t in (tq, tk, tv):
+                    t.copy_(torch.randn(t.shape, device="cuda", generator=gen).to(torch.bfloat16))
+            o_graph.fill_(float("nan"))
+            da.distr_attn_fwd_ex(tq, tk, tv, o_eager, da.make_params(tq, tk, tv, workspace=ws_eager, **common))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(o_graph.view(torch.int16), o_eager.view(torch.int16)), (cfg.name, rep)
