@@ -106,6 +106,26 @@ def _shapes(q, k, v):
     return B, H, k.shape[1], N, d
 
 
+def _check_out(q, o):
+    """o is written by the kernels with q's shape and element type: anything else would be
+    written out of bounds on the device."""
+    if tuple(o.shape) != tuple(q.shape) or o.dtype != q.dtype:
+        raise ValueError("o must have the shape and dtype of q")
+    if not o.is_cuda or not o.is_contiguous():
+        raise ValueError("o must be contiguous and on the GPU")
+
+
+def _check_buffer(t, name, min_bytes):
+    """An optional device buffer the library reads or writes `min_bytes` of."""
+    if t is None:
+        return
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous and on the GPU")
+    have = t.numel() * t.element_size()
+    if have < min_bytes:
+        raise ValueError(f"{name} holds {have} bytes, {min_bytes} needed")
+
+
 def make_params(q, k, v, Br, Bc=64, n_groups=None, causal=False, lsh_seed=0, n_planes=0,
                 softmax_scale=0.0, gray_mode=0, workspace=None, perm_out=None, hash_out=None,
                 perm_in=None, kt_in=None):
@@ -120,6 +140,11 @@ def make_params(q, k, v, Br, Bc=64, n_groups=None, causal=False, lsh_seed=0, n_p
     p.softmax_scale = softmax_scale
     p.gray_mode = gray_mode
     p.stream = _current_stream().value
+    n_table = B * H * ((N + Br - 1) // Br) * d if Br > 0 else 0
+    _check_buffer(workspace, "workspace", 0)
+    _check_buffer(perm_out, "perm_out", n_table)
+    _check_buffer(hash_out, "hash_out", 4 * n_table)
+    _check_buffer(perm_in, "perm_in", n_table)
     if workspace is not None:
         p.workspace = workspace.data_ptr()
         p.workspace_bytes = workspace.numel() * workspace.element_size()
@@ -127,6 +152,8 @@ def make_params(q, k, v, Br, Bc=64, n_groups=None, causal=False, lsh_seed=0, n_p
     p.hash_out = hash_out.data_ptr() if hash_out is not None else None
     p.perm_in = perm_in.data_ptr() if perm_in is not None else None
     p.kt_in = kt_in.data_ptr() if kt_in is not None else None
+    if kt_in is not None:
+        _check_buffer(kt_in, "kt_in", distr_attn_kt_bytes(p))
     return p
 
 
@@ -135,6 +162,7 @@ def distr_attn_fwd(q, k, v, o, Br, Bc, n_groups, lsh_seed=0, causal=False):
     B, H, Hkv, N, d = _shapes(q, k, v)
     if _dtype_code(q) != DA_BF16:
         raise TypeError("the short form takes bf16 tensors; use distr_attn_fwd_ex for float")
+    _check_out(q, o)
     lib().distr_attn_set_stream(_current_stream())
     _check(lib().distr_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), B, H, Hkv, N, d, Br, Bc,
                                 n_groups, lsh_seed, int(bool(causal))))
@@ -145,18 +173,28 @@ def distr_attn_exact_fwd(q, k, v, o, Br, Bc, causal=False):
     B, H, Hkv, N, d = _shapes(q, k, v)
     if _dtype_code(q) != DA_BF16:
         raise TypeError("the short form takes bf16 tensors; use distr_attn_exact_fwd_ex for float")
+    _check_out(q, o)
     lib().distr_attn_set_stream(_current_stream())
     _check(lib().distr_attn_exact_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), B, H, Hkv, N, d, Br, Bc,
                                       int(bool(causal))))
     return o
 
 
+def _check_ex(q, k, v, o, params):
+    B, H, Hkv, N, d = _shapes(q, k, v)
+    _check_out(q, o)
+    if (params.B, params.H, params.Hkv, params.N, params.d, params.dtype) != (B, H, Hkv, N, d, _dtype_code(q)):
+        raise ValueError("params were made for tensors of another shape or dtype")
+
+
 def distr_attn_fwd_ex(q, k, v, o, params):
+    _check_ex(q, k, v, o, params)
     _check(lib().distr_attn_fwd_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(o), ctypes.byref(params)))
     return o
 
 
 def distr_attn_exact_fwd_ex(q, k, v, o, params):
+    _check_ex(q, k, v, o, params)
     _check(lib().distr_attn_exact_fwd_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(o), ctypes.byref(params)))
     return o
 
@@ -166,6 +204,9 @@ def distr_attn_lsh_group(q, params):
 
 
 def distr_attn_key_prepass(k, kt_out, params):
+    if not k.is_cuda or not k.is_contiguous():
+        raise ValueError("k must be contiguous and on the GPU")
+    _check_buffer(kt_out, "kt_out", distr_attn_kt_bytes(params))
     _check(lib().distr_attn_key_prepass(_ptr(k), _ptr(kt_out), ctypes.byref(params)))
     return kt_out
 

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <mutex>
+#include <vector>
 
 #include "da_common.h"
 
@@ -14,9 +15,14 @@ namespace {
 thread_local char g_err[256] = "";
 std::atomic<void*> g_stream{nullptr};
 
+constexpr int kMaxDevices = 16;
 std::mutex g_ws_mutex;
-void* g_ws_ptr[16] = {nullptr};     // library-owned workspace, one per device
-size_t g_ws_bytes[16] = {0};
+void* g_ws_ptr[kMaxDevices] = {nullptr};     // library-owned workspace, one per device
+size_t g_ws_bytes[kMaxDevices] = {0};
+// Buffers the library-owned workspace has outgrown. Work enqueued by earlier calls (or by a
+// thread that fetched the pointer just before the growth) may still use them, so they are kept
+// until distr_attn_release instead of being freed inside a forward call.
+std::vector<void*> g_ws_retired[kMaxDevices];
 
 int fail(int code, const char* fmt, ...) {
   va_list ap;
@@ -91,12 +97,20 @@ size_t kt_bytes(const Resolved& r) {
   return (n + 255) & ~(size_t)255;
 }
 
-// Device scratch of the distr path: [K^T copy | permutation table], from the caller's workspace
-// or from the library-owned one. The table goes to perm_out instead when the caller gave one.
-int get_scratch(const da_params* p, const Resolved& r, bool need_perm, uint8_t** perm, void** kt) {
-  const size_t kt_need = kt_bytes(r);
-  const size_t need = kt_need + perm_bytes(r);
+// Device scratch of the distr path: [K^T copy | permutation table]. Only the parts this call
+// writes are asked for: no K^T copy when the caller brings kt_in (or on the float path), no
+// table when the grouping comes from perm_in, goes to perm_out, or stays inside the attention
+// kernel. Source: the caller's workspace or the library-owned buffer.
+int get_scratch(const da_params* p, const Resolved& r, bool need_table, uint8_t** perm, void** kt) {
+  const size_t kt_need = (r.dtype == DA_BF16 && !p->kt_in) ? kt_bytes(r) : 0;
+  const size_t perm_need = need_table ? perm_bytes(r) : 0;
+  const size_t need = kt_need + perm_need;
   char* base = nullptr;
+  if (need == 0) {
+    *kt = nullptr;
+    *perm = nullptr;
+    return DA_OK;
+  }
   if (p->workspace) {
     if (p->workspace_bytes < need)
       return fail(DA_ERR_WORKSPACE, "workspace of %zu bytes, %zu needed", p->workspace_bytes, need);
@@ -104,26 +118,25 @@ int get_scratch(const da_params* p, const Resolved& r, bool need_perm, uint8_t**
     base = (char*)p->workspace;
   } else {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(DA_ERR_HIP, "hipGetDevice failed");
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return fail(DA_ERR_HIP, "hipGetDevice failed");
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     if (g_ws_bytes[dev] < need) {
-      if (g_ws_ptr[dev]) {
-        // the old buffer may still be read by enqueued work
-        if (hipDeviceSynchronize() != hipSuccess) return fail(DA_ERR_HIP, "hipDeviceSynchronize failed");
-        (void)hipFree(g_ws_ptr[dev]);
-        g_ws_ptr[dev] = nullptr;
-        g_ws_bytes[dev] = 0;
-      }
+      // Growing allocates: not allowed while the stream is being captured into a graph.
+      hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+      if (hipStreamIsCapturing(r.stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
+        return fail(DA_ERR_WORKSPACE, "the library-owned workspace would have to grow to %zu bytes while the stream is "
+                    "being captured: pass a workspace, or run the call once before capturing", need);
       void* ptr = nullptr;
       hipError_t e = hipMalloc(&ptr, need);
       if (e != hipSuccess) return fail(DA_ERR_WORKSPACE, "hipMalloc(%zu) failed: %s", need, hipGetErrorString(e));
+      if (g_ws_ptr[dev]) g_ws_retired[dev].push_back(g_ws_ptr[dev]);
       g_ws_ptr[dev] = ptr;
       g_ws_bytes[dev] = need;
     }
     base = (char*)g_ws_ptr[dev];
   }
   *kt = kt_need ? (void*)base : nullptr;
-  *perm = (need_perm && p->perm_out) ? p->perm_out : (uint8_t*)(base + kt_need);
+  *perm = perm_need ? (uint8_t*)(base + kt_need) : nullptr;
   return DA_OK;
 }
 
@@ -155,17 +168,17 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
     distr = false;
   }
   if (distr) {
-    uint8_t* table = nullptr;
-    rc = get_scratch(p, r, p->perm_in == nullptr, &table, &kt);
-    if (rc) return rc;
     // bf16 path, up to 16 projections, no table asked for: the attention kernel hashes and groups
     // its own Q block in its prologue (same arithmetic as the LSH kernel) and no table is written.
     const bool lsh_in_kernel = r.dtype == DA_BF16 && !p->perm_in && !p->perm_out && !p->hash_out && r.pb.n_planes <= 16;
+    const bool run_lsh = !p->perm_in && !lsh_in_kernel;
+    uint8_t* table = nullptr;
+    rc = get_scratch(p, r, run_lsh && !p->perm_out, &table, &kt);
+    if (rc) return rc;
     if (p->perm_in) {
       perm = p->perm_in;
-    } else if (lsh_in_kernel) {
-      perm = nullptr;
-    } else {
+    } else if (run_lsh) {
+      if (p->perm_out) table = p->perm_out;
       rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, table, p->hash_out, r.stream), "lsh_group launch");
       if (rc) return rc;
       perm = table;
@@ -267,10 +280,13 @@ int distr_attn_release(void) {
   int rc = DA_OK;
   int cur = 0;
   bool have_cur = hipGetDevice(&cur) == hipSuccess;
-  for (int dev = 0; dev < 16; ++dev) {
-    if (!g_ws_ptr[dev]) continue;
-    if (hipSetDevice(dev) != hipSuccess || hipDeviceSynchronize() != hipSuccess || hipFree(g_ws_ptr[dev]) != hipSuccess)
-      rc = fail(DA_ERR_HIP, "release: freeing the workspace of device %d failed", dev);
+  for (int dev = 0; dev < kMaxDevices; ++dev) {
+    if (!g_ws_ptr[dev] && g_ws_retired[dev].empty()) continue;
+    bool ok = hipSetDevice(dev) == hipSuccess && hipDeviceSynchronize() == hipSuccess;
+    if (ok && g_ws_ptr[dev]) ok = hipFree(g_ws_ptr[dev]) == hipSuccess;
+    for (void* old : g_ws_retired[dev]) ok = ok && hipFree(old) == hipSuccess;
+    if (!ok) rc = fail(DA_ERR_HIP, "release: freeing the workspace of device %d failed", dev);
+    g_ws_retired[dev].clear();
     g_ws_ptr[dev] = nullptr;
     g_ws_bytes[dev] = 0;
   }

@@ -134,29 +134,13 @@ struct Cfg {
   static constexpr int KSTEPS = KRED / 16;        // MFMA steps of the score product
 };
 
-// Tuning switches (compile-time; the defaults are what the library ships with).
-#ifndef DA_HINTS
-#define DA_HINTS 0          // 1: force an MFMA / LDS / vector interleave with scheduling groups (measured: no gain)
-#endif
-#ifndef DA_KPF
-#define DA_KPF 4            // LDS operand reads issued ahead of the first MFMA of a phase
-#endif
-#ifndef DA_WAVES_PER_EU
-#define DA_WAVES_PER_EU 2   // occupancy target (waves per SIMD) given to the register allocator
-#endif
-// Ablation switches (never defined in the shipped build; results are wrong with any of them):
-// DA_ABL_NOKREAD / DA_ABL_NOVREAD replace the LDS operand reads of the score / P.V product by
-// registers, DA_ABL_NOEXP drops the exponentials, DA_ABL_NOBARRIER the per-tile barrier,
-// DA_ABL_NOFUSE the per-tile key fusion. Timing the kernel with one of them removed tells what
-// that part costs; every access stays in bounds and every loop keeps its trip count.
-
 // Rows whose running maximum moved by less than this (in log2 units) keep their old reference
 // maximum: P is then at most 2^kTau, the sums stay exact ratios, and the accumulator rescale
 // (one multiply per accumulator register) is skipped for almost every tile.
 constexpr float kTau = 8.0f;
 
 template <int D, int BR, int KRED, bool DISTR, int NG>
-__global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
+__global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     bf16* __restrict__ o, const uint8_t* __restrict__ perm, const f16* __restrict__ kt, int Npad,
     int H, int Hkv, int N, int Tq, int causal, float scale_log2e, int total_units, int n_planes,
@@ -229,7 +213,8 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
     }
     if (perm != nullptr) {
       const size_t pbase = ((size_t)bh * Tq + t) * D;
-      for (int i = tid; i < D; i += C::T) perm_lds[i] = perm[pbase + i];
+      // D is a power of two: an out-of-range entry of a caller's table cannot index past a row
+      for (int i = tid; i < D; i += C::T) perm_lds[i] = perm[pbase + i] & (D - 1);
     } else {
       // ---- LSH hash-and-group of this Q block inside the workgroup (Sec. 3.2, 3.3) -------------
       // Same arithmetic as the stand-alone LSH kernel (float, one fused multiply-add per row,
@@ -453,15 +438,11 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
 #pragma unroll
       for (int s = 0; s < C::KSTEPS; ++s) {
         kx8 a;
-#ifdef DA_ABL_NOKREAD
-        a = qop[(s + 1) % C::KSTEPS];
-#else
         if constexpr (DISTR)
           a = lds_read_tr_pair<kx8>(base + ka_off[mb * 2] + s * 16 * C::KTROWB,
                                     base + ka_off[mb * 2 + 1] + s * 16 * C::KTROWB);
         else
           a = *(const kx8*)(base + ka_off[s] + mb * 32 * C::ROWB);
-#endif
         sacc[mb] = mfma_32x32x16(a, qop[s], sacc[mb]);
       }
     }
@@ -506,14 +487,11 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
   //   phase X: scores of tile it+1 into `sn` (matrix pipe)  ||  exp, bf16 P, row sum of `sc` (vector ALUs)
   //   phase Y: O^T += V^T . P^T for tile it (matrix pipe)    ||  mask and row maximum of `sn` (vector ALUs)
   // then the rare reference move for tile it+1, the LDS stores of the prefetched tiles, one barrier.
-  // The scheduling hints at the end ask the compiler to interleave the two instruction streams
-  // instead of emitting them one after the other.
   auto body = [&](auto mask_next_c, auto next_c, int it, int par, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
     constexpr bool HAS_NEXT = decltype(next_c)::value;
     // The buffers these loads fill were last read in the previous iteration, which every wave
     // has left (barrier): K(it+2) replaces K(it), V(it+1) replaces V(it-1).
     if constexpr (HAS_NEXT) {
-#ifndef DA_ABL_NOFUSE
       // distr: the pieces of K^T(it+2), loaded during the previous iteration, are summed now
       // into the buffer K_f^T(it) has left, and the loads of K^T(it+3) take their registers.
       // Nothing in this iteration depends on the fusion: it runs beside the MFMAs.
@@ -521,7 +499,6 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
         fuse_pieces(par, piece);       // K^T(it+2), loaded during the previous iteration
         load_pieces(it + 3, piece);
       }
-#endif
       if constexpr (!DISTR) dma_tile(k_rsrc, it + 2, dma_k, kx_buf(par));
       dma_tile(v_rsrc, it + 1, dma_v, v_buf(par ^ 1));
     }
@@ -537,13 +514,8 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
-#ifdef DA_ABL_NOEXP
-          float p0 = __builtin_fmaf(sc[mb][i], scale_log2e, -m_ref);
-          float p1 = __builtin_fmaf(sc[mb][i + 1], scale_log2e, -m_ref);
-#else
           float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mb][i], scale_log2e, -m_ref));
           float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mb][i + 1], scale_log2e, -m_ref));
-#endif
           bf16x2 pr = {(bf16)p0, (bf16)p1};
           pop[mb * 2 + (i >> 3)][i & 7] = pr[0];
           pop[mb * 2 + (i >> 3)][(i & 7) + 1] = pr[1];
@@ -560,57 +532,17 @@ __global__ __launch_bounds__(BR * 2, DA_WAVES_PER_EU) void attn_bf16_kernel(
 #pragma unroll
       for (int mb = 0; mb < D / 32; ++mb) {
         const char* p0 = vb + va_off[mb] + 16 * tt * C::ROWB;
-#ifdef DA_ABL_NOVREAD
-        bf16x8 a = pop[(tt + mb + 1) & 3];
-        (void)p0;
-#else
         bf16x8 a = lds_read_tr_pair<bf16x8>(p0, p0 + 8 * C::ROWB);
-#endif
         oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pop[tt], oacc[mb], 0, 0, 0);
       }
     }
     float mt_next = 0.0f;
     if constexpr (HAS_NEXT) mt_next = row_max(mask_next_c, it + 1, sn);
-    // ---- scheduling hints (groups are filled in this order) -----------------------------------
-    // One MFMA occupies the issue port for 8 cycles and the matrix pipe for 32: up to 6 vector
-    // instructions fit beside it. Operands are fetched from LDS four MFMAs ahead.
-#if DA_HINTS
-    {
-      constexpr int N_QK = HAS_NEXT ? 2 * C::KSTEPS : 0;
-      constexpr int N_PV = D / 8;
-      constexpr int VALU_PER_MFMA = ((DA_HINTS == 2 ? 118 : 150) + N_QK + N_PV - 1) / (N_QK + N_PV);
-      constexpr int PF = DA_KPF < N_QK ? DA_KPF : N_QK;
-      __builtin_amdgcn_sched_group_barrier(0x100, HAS_NEXT ? PF : 2 * DA_KPF, 0);
-#if DA_HINTS == 2   // vector work first, while the first operands travel
-      __builtin_amdgcn_sched_group_barrier(0x402, 32, 0);
-#endif
-#pragma unroll
-      for (int i = 0; i < N_QK - PF; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one score MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        // a K operand, PF MFMAs ahead
-        __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER_MFMA, 0);
-      }
-#pragma unroll
-      for (int i = 0; i < PF; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one score MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);        // K operands are all in: first V operands
-        __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER_MFMA, 0);
-      }
-#pragma unroll
-      for (int i = 0; i < N_PV; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one P.V MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);        // next V operand
-        __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER_MFMA, 0);
-      }
-    }
-#endif
     if constexpr (HAS_NEXT) {
       move_reference(mt_next);
       dma_wait();              // this wave's direct loads have landed
     }
-#ifndef DA_ABL_NOBARRIER
     __syncthreads();
-#endif
   };
 
   // ---- prologue: tiles 0 (K, V) and 1 (K) into LDS, scores of tile 0 ---------------------------

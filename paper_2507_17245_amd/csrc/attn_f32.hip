@@ -44,7 +44,8 @@ __global__ __launch_bounds__(BR * kF32Lanes) void attn_f32_kernel(
   const float* vh = v + ((size_t)(b * Hkv + hk) * N) * D;
 
   if (distr)
-    for (int i = tid; i < D; i += T) perm_lds[i] = perm[(size_t)blockIdx.x * D + i];
+    // D is a power of two: an out-of-range entry of a caller's table cannot index past a row
+    for (int i = tid; i < D; i += T) perm_lds[i] = perm[(size_t)blockIdx.x * D + i] & (D - 1);
   __syncthreads();
   const bool active = row < rows;
   const int i_abs = r0 + row;

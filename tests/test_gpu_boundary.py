@@ -1,0 +1,124 @@
+"""GPU parity of the boundary's options against the CPU oracle: a caller-chosen softmax scale
+(1.0 is the literal S = Q K^T of Sec. 2.1), a caller-provided grouping table, the input-range
+limits of the half-precision reduced product, and the block order used for large causal problems."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def small(name, **kw):
+    return W.CONFIGS[name].scaled(**kw)
+
+
+@pytest.mark.parametrize("scale", [1.0, 0.05, 0.3])
+@pytest.mark.parametrize("base,kw", [("vit", dict(B=1, H=3, Hkv=3, N=150)),
+                                     ("long", dict(H=2, Hkv=1, N=300)),
+                                     ("tiny", dict(N=130))])
+def test_softmax_scale(base, kw, scale):
+    import gpu_util as U
+    cfg = small(base, **kw)
+    q, k, v = W.make(cfg)
+    if scale == 1.0:
+        # unscaled logits of N(0,1) data have a spread of sqrt(d): bring the inputs down so that
+        # the softmax is not one-hot and the comparison says something
+        q = W.round_to_bf16(q * 0.5) if cfg.dtype == "bf16" else q * np.float32(0.5)
+        k = W.round_to_bf16(k * 0.5) if cfg.dtype == "bf16" else k * np.float32(0.5)
+    p = U.oracle_params(cfg, scale=scale)
+    print(f"case {cfg} scale {scale}", flush=True)
+    o_gpu, perm_gpu, _ = U.run_gpu(cfg, q, k, v, distr=True, want_tables=True, scale=scale)
+    assert np.array_equal(perm_gpu, oracle.lsh_group(q, p)[1])
+    U.assert_close(o_gpu, oracle.distr_fwd(q, k, v, p), cfg.dtype, "distr")
+    o_self, _, _ = U.run_gpu(cfg, q, k, v, distr=True, scale=scale)
+    assert np.array_equal(o_self, o_gpu)
+    o_ex, _, _ = U.run_gpu(cfg, q, k, v, distr=False, scale=scale)
+    U.assert_close(o_ex, oracle.exact_fwd(q, k, v, p), cfg.dtype, "exact")
+    # the scale really reached the kernels: the default-scale output is something else
+    o_def, _, _ = U.run_gpu(cfg, q, k, v, distr=False)
+    assert np.abs(o_def - o_ex).max() > 1e-2
+
+
+@pytest.mark.parametrize("base,kw", [("vit", dict(B=2, H=2, Hkv=2, N=200)),
+                                     ("llama", dict(H=4, Hkv=2, N=300)),
+                                     ("mid", dict(B=1, H=2, Hkv=2, N=260, n_groups=32)),
+                                     ("tiny", dict(N=200))])
+def test_caller_grouping_table(base, kw):
+    """perm_in replaces the LSH stage: a random valid table per query block, against the oracle
+    run with the same table."""
+    import gpu_util as U
+    cfg = small(base, **kw)
+    q, k, v = W.make(cfg)
+    rng = np.random.default_rng(42)
+    perm = np.stack([rng.permutation(cfg.d) for _ in range(cfg.B * cfg.H * cfg.Tq)]).astype(np.uint8)
+    perm = perm.reshape(cfg.B, cfg.H, cfg.Tq, cfg.d)
+    p = U.oracle_params(cfg)
+    print(f"case {cfg} perm_in", flush=True)
+    o_gpu, _, _ = U.run_gpu(cfg, q, k, v, distr=True, perm_in=perm)
+    U.assert_close(o_gpu, oracle.distr_fwd(q, k, v, p, perm=perm), cfg.dtype, "distr with perm_in")
+    # the table mattered: the LSH grouping gives another result
+    o_lsh, _, _ = U.run_gpu(cfg, q, k, v, distr=True)
+    assert np.abs(o_lsh - o_gpu).max() > 1e-3
+
+
+def test_half_range_clamp_of_the_reduced_product():
+    """bf16 DistrAttention holds Q_r and K_f in half precision: |q| beyond 65504 and |k| beyond
+    65504 / G* are clamped (documented input limit). The oracle, fed the clamped values and the
+    grouping of the unclamped Q (the LSH stage sees the original values), must agree."""
+    import gpu_util as U
+    for n_groups in (32, 16):
+        cfg = small("vit", B=1, H=2, Hkv=2, N=150, n_groups=n_groups)
+        G = cfg.d // n_groups
+        q, k, v = W.make(cfg)
+        q, k = q.copy(), k.copy()
+        big = np.float32(2.0 ** 20)
+        q[0, 0, 3, 5], q[0, 1, 70, 9], q[0, 0, 149, 60] = big, -big, big
+        k[0, 0, 10, 7], k[0, 1, 100, 33], k[0, 0, 64, 0] = big, -big, -big
+        p = U.oracle_params(cfg)
+        perm = oracle.lsh_group(q, p)[1]
+        qc = np.clip(q, -65504.0, 65504.0).astype(np.float32)
+        kc = np.clip(k, -65504.0 / G, 65504.0 / G).astype(np.float32)
+        print(f"case {cfg} clamp", flush=True)
+        o_gpu, perm_gpu, _ = U.run_gpu(cfg, q, k, v, distr=True, want_tables=True)
+        assert np.array_equal(perm_gpu, perm)
+        U.assert_close(o_gpu, oracle.distr_fwd(qc, kc, v, p, perm=perm), "bf16", f"clamped, G*={G}")
+
+
+@pytest.mark.parametrize("shift", [-8, 10])
+def test_inputs_far_from_unit_scale(shift):
+    """Q and K scaled by a power of two with the softmax scale compensating: the scores are the
+    same numbers, the half-precision operands of the reduced product sit elsewhere in half's
+    exponent range (documented range: 2^-14 <= |x| <= 65504 / G* keeps full precision)."""
+    import gpu_util as U
+    for base, kw in (("llama", dict(H=4, Hkv=2, N=300)), ("mid", dict(B=1, H=2, Hkv=2, N=260))):
+        cfg = small(base, **kw)
+        q, k, v = W.make(cfg)
+        f = np.float32(2.0 ** shift)
+        q2, k2 = q * f, k * f                     # exact: powers of two keep bf16 values on the grid
+        scale = float(1.0 / np.sqrt(cfg.d) / (float(f) * float(f)))
+        p = U.oracle_params(cfg, scale=scale)
+        print(f"case {cfg} shift {shift}", flush=True)
+        o_gpu, perm_gpu, _ = U.run_gpu(cfg, q2, k2, v, distr=True, want_tables=True, scale=scale)
+        assert np.array_equal(perm_gpu, oracle.lsh_group(q2, p)[1])
+        U.assert_close(o_gpu, oracle.distr_fwd(q2, k2, v, p), "bf16", "distr")
+        o_ex, _, _ = U.run_gpu(cfg, q2, k2, v, distr=False, scale=scale)
+        U.assert_close(o_ex, oracle.exact_fwd(q2, k2, v, p), "bf16", "exact")
+
+
+def test_head_major_causal_order_on_every_block():
+    """Causal problems of more than 2048 query blocks are dispatched head by head (longest block
+    first inside a head) instead of longest-first over all heads: every block of such a problem
+    against the oracle."""
+    import gpu_util as U
+    cfg = small("vit", B=4, H=16, Hkv=16, N=2100, causal=True, Br=64)
+    assert cfg.B * cfg.H * cfg.Tq > 2048
+    q, k, v = W.make(cfg)
+    p = U.oracle_params(cfg)
+    print(f"case {cfg}", flush=True)
+    o_gpu, perm_gpu, _ = U.run_gpu(cfg, q, k, v, distr=True, want_tables=True)
+    assert np.array_equal(perm_gpu, oracle.lsh_group(q, p)[1])
+    U.assert_close(o_gpu, oracle.distr_fwd(q, k, v, p), "bf16", "distr")
+    o_ex, _, _ = U.run_gpu(cfg, q, k, v, distr=False)
+    U.assert_close(o_ex, oracle.exact_fwd(q, k, v, p), "bf16", "exact")

@@ -12,6 +12,17 @@ import workloads as W
 pytestmark = pytest.mark.gpu
 
 CASES = [("vit", 32), ("llama", 32), ("mid", 128), ("mid", 64), ("mid", 32), ("long", 64)]
+# (max-abs, mean-abs) against the oracle on the sampled blocks, as measured when the kernels were
+# last tuned: {case: (distr, exact)}. The test fails beyond three times these, far inside the
+# 2e-2 / 2e-3 bar, so that a loss of accuracy shows up even where the bar is loose.
+RECORDED = {
+    ("vit", 32): ((2.5e-3, 2.1e-4), (2.5e-3, 2.1e-4)),
+    ("llama", 32): ((1.3e-2, 7.2e-4), (1.3e-2, 7.2e-4)),
+    ("mid", 128): ((9.7e-4, 3.8e-5), (9.7e-4, 3.8e-5)),
+    ("mid", 64): ((9.7e-4, 3.8e-5), (9.7e-4, 3.8e-5)),
+    ("mid", 32): ((9.7e-4, 3.8e-5), (9.7e-4, 3.8e-5)),
+    ("long", 64): ((7.7e-3, 1.4e-4), (7.7e-3, 1.4e-4)),
+}
 _inputs = {}
 
 
@@ -49,7 +60,7 @@ def test_full_size_parity(name, n_groups):
     valid = ~np.isnan(ref)
     got = gather(o_gpu)
     assert np.array_equal(~np.isnan(got), valid)
-    mx, mean = U.assert_close(got[valid], ref[valid], cfg.dtype, "distr")
+    mx, mean = U.assert_close(got[valid], ref[valid], cfg.dtype, "distr", recorded=RECORDED[(name, n_groups)][0])
     print(f"  distr: max-abs {mx:.3g} mean-abs {mean:.3g}", flush=True)
     assert np.isfinite(o_gpu).all()
     # the call bench.py times asks for no tables: the attention kernel then does the LSH stage of
@@ -59,7 +70,7 @@ def test_full_size_parity(name, n_groups):
     del o_gpu, o_self
     o_ex, _, _ = U.run_gpu(cfg, q, k, v, distr=False)
     ref_ex = oracle.exact_fwd_tiles(q, k, v, p, tiles)
-    mx, mean = U.assert_close(gather(o_ex)[valid], ref_ex[valid], cfg.dtype, "exact")
+    mx, mean = U.assert_close(gather(o_ex)[valid], ref_ex[valid], cfg.dtype, "exact", recorded=RECORDED[(name, n_groups)][1])
     print(f"  exact: max-abs {mx:.3g} mean-abs {mean:.3g}", flush=True)
     assert np.isfinite(o_ex).all()
     if n_groups == cfg.d:   # groups of one channel: the approximation is the exact product (Sec. 3.1)

@@ -120,3 +120,74 @@ def test_bench_refuses_more_than_one_gpu_and_reads_its_traffic_figure():
     assert len(lines) == 1
     rec = json.loads(lines[0].split(":", 1)[1])
     assert rec["workload"] == "long" and rec["hbm_bytes_per_launch"] > 5e8
+
+
+class _FakeTensor:
+    """Stand-in with the attributes the binding inspects; its pointer is never dereferenced because
+    every case below is rejected by the binding before the library is called."""
+
+    def __init__(self, shape, dtype=None, cuda=True, contiguous=True, itemsize=2):
+        import torch
+        self.shape = tuple(shape)
+        self.dtype = torch.bfloat16 if dtype is None else dtype
+        self.is_cuda = cuda
+        self._contiguous = contiguous
+        self._itemsize = itemsize
+
+    def dim(self):
+        return len(self.shape)
+
+    def is_contiguous(self):
+        return self._contiguous
+
+    def numel(self):
+        return int(np.prod(self.shape))
+
+    def element_size(self):
+        return self._itemsize
+
+    def data_ptr(self):
+        return 0x1000
+
+
+def test_binding_rejects_bad_output_and_side_buffers(monkeypatch):
+    """The binding checks o and the optional device buffers on the host: a small or strided buffer
+    would otherwise be written or read past its end on the device."""
+    import torch
+    monkeypatch.setattr(da, "_current_stream", lambda: ctypes.c_void_p(0))
+    q = _FakeTensor((1, 4, 100, 64))
+    k = _FakeTensor((1, 2, 100, 64))
+    good = dict(Br=64, n_groups=32)
+    p = da.make_params(q, k, k, **good)
+    for bad_o in (_FakeTensor((1, 4, 99, 64)), _FakeTensor((1, 4, 100, 64), dtype=torch.float32, itemsize=4),
+                  _FakeTensor((1, 4, 100, 64), cuda=False), _FakeTensor((1, 4, 100, 64), contiguous=False)):
+        for call in (lambda o: da.distr_attn_fwd_ex(q, k, k, o, p), lambda o: da.distr_attn_exact_fwd_ex(q, k, k, o, p),
+                     lambda o: da.distr_attn_fwd(q, k, k, o, 64, 64, 32), lambda o: da.distr_attn_exact_fwd(q, k, k, o, 64, 64)):
+            with pytest.raises(ValueError):
+                call(bad_o)
+    n_table = 1 * 4 * 2 * 64
+    small = _FakeTensor((n_table - 1,), dtype=torch.uint8, itemsize=1)
+    for name in ("perm_out", "perm_in"):
+        with pytest.raises(ValueError, match=name):
+            da.make_params(q, k, k, **good, **{name: small})
+    with pytest.raises(ValueError, match="hash_out"):
+        da.make_params(q, k, k, **good, hash_out=_FakeTensor((n_table - 1,), dtype=torch.int32, itemsize=4))
+    with pytest.raises(ValueError, match="perm_out"):
+        da.make_params(q, k, k, **good, perm_out=_FakeTensor((n_table,), dtype=torch.uint8, itemsize=1, cuda=False))
+    with pytest.raises(ValueError, match="kt_in"):
+        da.make_params(q, k, k, **good, kt_in=_FakeTensor((100,), dtype=torch.uint8, itemsize=1))
+    # params made for other tensors are refused
+    q2 = _FakeTensor((1, 4, 101, 64))
+    k2 = _FakeTensor((1, 2, 101, 64))
+    with pytest.raises(ValueError, match="another shape"):
+        da.distr_attn_fwd_ex(q2, k2, k2, _FakeTensor((1, 4, 101, 64)), p)
+
+
+def test_workspace_need_follows_what_the_call_writes():
+    """kt_in removes the K^T copy from the scratch a call needs and perm_in / the in-kernel LSH
+    stage remove the table: a workspace that only holds the rest is accepted (the call then fails
+    later, on the host, at the misaligned kt_in -- nothing is launched)."""
+    L = da.lib()
+    p = _params(workspace=0x3000 << 8, workspace_bytes=16, kt_in=0x1001)
+    assert L.distr_attn_fwd_ex(FAKE, FAKE, FAKE, FAKE_O, ctypes.byref(p)) == da.DA_ERR_INVALID_ARG
+    assert b"kt_in" in L.distr_attn_last_error()
