@@ -121,6 +121,22 @@ size_t distr_attn_workspace_bytes(const da_params *p);
  */
 int distr_attn_hyperplanes(uint64_t seed, int n_planes, int Br, float *host_out);
 
+/*
+ * distr_attn_fwd_ex for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc. Same arguments, same kernels, same
+ * result; the scratch the forward needs (the transposed copy of K, and the permutation table
+ * when the LSH stage runs as a kernel of its own) lives in a fixed device array of
+ * DISTR_ATTN_NOALLOC_MAX_BYTES inside the library instead of a workspace, so the call allocates
+ * and frees nothing (p->workspace is ignored). Each GPU the library runs on holds its own copy
+ * of the array until the process ends. A problem whose scratch exceeds the array is refused
+ * with DA_ERR_WORKSPACE before anything is launched (kt_in removes the K^T part of the need).
+ * All calls on one GPU share the array: calls that overlap in time on one GPU race; calls
+ * queued on one stream do not.
+ */
+#define DISTR_ATTN_NOALLOC_MAX_BYTES (32u << 20)
+int distr_attn_fwd_noalloc(const void *q, const void *k, const void *v, void *o, const da_params *p);
+size_t distr_attn_noalloc_max_bytes(void);
+
 /* Stream used when da_params.stream is NULL and by the short-form entry points (process-wide). */
 int distr_attn_set_stream(void *hip_stream);
 

@@ -16,6 +16,7 @@ DA_BF16, DA_F32 = 0, 1
 
 EXPORTS = (
     "distr_attn_fwd", "distr_attn_exact_fwd", "distr_attn_fwd_ex", "distr_attn_exact_fwd_ex",
+    "distr_attn_fwd_noalloc", "distr_attn_noalloc_max_bytes",
     "distr_attn_lsh_group", "distr_attn_key_prepass", "distr_attn_kt_bytes",
     "distr_attn_workspace_bytes", "distr_attn_hyperplanes",
     "distr_attn_set_stream", "distr_attn_release", "distr_attn_last_error", "distr_attn_version",
@@ -54,7 +55,8 @@ def lib():
         vp, ci, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64
         L.distr_attn_fwd.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, u64, ci]
         L.distr_attn_exact_fwd.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci]
-        for name in ("distr_attn_fwd_ex", "distr_attn_exact_fwd_ex"):
+        L.distr_attn_noalloc_max_bytes.restype = ctypes.c_size_t
+        for name in ("distr_attn_fwd_ex", "distr_attn_exact_fwd_ex", "distr_attn_fwd_noalloc"):
             getattr(L, name).argtypes = [vp, vp, vp, vp, ctypes.POINTER(DaParams)]
         L.distr_attn_lsh_group.argtypes = [vp, ctypes.POINTER(DaParams)]
         L.distr_attn_key_prepass.argtypes = [vp, vp, ctypes.POINTER(DaParams)]
@@ -191,6 +193,17 @@ def distr_attn_fwd_ex(q, k, v, o, params):
     _check_ex(q, k, v, o, params)
     _check(lib().distr_attn_fwd_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(o), ctypes.byref(params)))
     return o
+
+
+def distr_attn_fwd_noalloc(q, k, v, o, params):
+    """distr_attn_fwd_ex on the library's fixed scratch array: allocates nothing."""
+    _check_ex(q, k, v, o, params)
+    _check(lib().distr_attn_fwd_noalloc(_ptr(q), _ptr(k), _ptr(v), _ptr(o), ctypes.byref(params)))
+    return o
+
+
+def distr_attn_noalloc_max_bytes():
+    return int(lib().distr_attn_noalloc_max_bytes())
 
 
 def distr_attn_exact_fwd_ex(q, k, v, o, params):

@@ -24,6 +24,14 @@ size_t g_ws_bytes[kMaxDevices] = {0};
 // until distr_attn_release instead of being freed inside a forward call.
 std::vector<void*> g_ws_retired[kMaxDevices];
 
+// Scratch of distr_attn_fwd_noalloc: a fixed device array, one copy per GPU the library is
+// loaded on, resident until the process ends. Host code never uses the array's name as an
+// address: the per-device address comes from hipGetSymbolAddress (static_scratch below).
+constexpr size_t kStaticScratchBytes = (size_t)DISTR_ATTN_NOALLOC_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
 int fail(int code, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -97,11 +105,26 @@ size_t kt_bytes(const Resolved& r) {
   return (n + 255) & ~(size_t)255;
 }
 
+// Address of the static scratch array on the current device (looked up once per device).
+int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return fail(DA_ERR_HIP, "hipGetDevice failed");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return fail(DA_ERR_HIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return DA_OK;
+}
+
 // Device scratch of the distr path: [K^T copy | permutation table]. Only the parts this call
 // writes are asked for: no K^T copy when the caller brings kt_in (or on the float path), no
 // table when the grouping comes from perm_in, goes to perm_out, or stays inside the attention
-// kernel. Source: the caller's workspace or the library-owned buffer.
-int get_scratch(const da_params* p, const Resolved& r, bool need_table, uint8_t** perm, void** kt) {
+// kernel. Source: the caller's workspace, the static array (no_alloc), or the library-owned buffer.
+int get_scratch(const da_params* p, const Resolved& r, bool need_table, bool no_alloc, uint8_t** perm, void** kt) {
   const size_t kt_need = (r.dtype == DA_BF16 && !p->kt_in) ? kt_bytes(r) : 0;
   const size_t perm_need = need_table ? perm_bytes(r) : 0;
   const size_t need = kt_need + perm_need;
@@ -111,7 +134,15 @@ int get_scratch(const da_params* p, const Resolved& r, bool need_table, uint8_t*
     *perm = nullptr;
     return DA_OK;
   }
-  if (p->workspace) {
+  if (no_alloc) {
+    if (need > kStaticScratchBytes)
+      return fail(DA_ERR_WORKSPACE, "distr_attn_fwd_noalloc: %zu bytes of scratch needed, the static array holds %zu "
+                  "(pass kt_in, or use distr_attn_fwd_ex with a workspace)", need, kStaticScratchBytes);
+    void* ptr = nullptr;
+    int rc = static_scratch(&ptr);
+    if (rc) return rc;
+    base = (char*)ptr;
+  } else if (p->workspace) {
     if (p->workspace_bytes < need)
       return fail(DA_ERR_WORKSPACE, "workspace of %zu bytes, %zu needed", p->workspace_bytes, need);
     if (((uintptr_t)p->workspace & 255u) != 0) return fail(DA_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
@@ -145,7 +176,8 @@ int check_launch(hipError_t e, const char* what) {
   return DA_OK;
 }
 
-int attention(const void* q, const void* k, const void* v, void* o, const da_params* p, bool distr) {
+int attention(const void* q, const void* k, const void* v, void* o, const da_params* p, bool distr,
+              bool no_alloc = false) {
   Resolved r;
   int rc = resolve(p, distr, &r);
   if (rc) return rc;
@@ -173,7 +205,7 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
     const bool lsh_in_kernel = r.dtype == DA_BF16 && !p->perm_in && !p->perm_out && !p->hash_out && r.pb.n_planes <= 16;
     const bool run_lsh = !p->perm_in && !lsh_in_kernel;
     uint8_t* table = nullptr;
-    rc = get_scratch(p, r, run_lsh && !p->perm_out, &table, &kt);
+    rc = get_scratch(p, r, run_lsh && !p->perm_out, no_alloc, &table, &kt);
     if (rc) return rc;
     if (p->perm_in) {
       perm = p->perm_in;
@@ -228,6 +260,12 @@ int distr_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, cons
 int distr_attn_exact_fwd_ex(const void* q, const void* k, const void* v, void* o, const da_params* p) {
   return attention(q, k, v, o, p, false);
 }
+
+int distr_attn_fwd_noalloc(const void* q, const void* k, const void* v, void* o, const da_params* p) {
+  return attention(q, k, v, o, p, true, true);
+}
+
+size_t distr_attn_noalloc_max_bytes(void) { return kStaticScratchBytes; }
 
 int distr_attn_lsh_group(const void* q, const da_params* p) {
   Resolved r;
