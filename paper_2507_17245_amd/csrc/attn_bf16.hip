@@ -134,10 +134,14 @@ struct Cfg {
   static constexpr int KSTEPS = KRED / 16;        // MFMA steps of the score product
 };
 
-// Rows whose running maximum moved by less than this (in log2 units) keep their old reference
-// maximum: P is then at most 2^kTau, the sums stay exact ratios, and the accumulator rescale
-// (one multiply per accumulator register) is skipped for almost every tile.
+// Lazy reference maximum. A row keeps its reference until one of its scores runs more than kTau
+// (log2 units) ahead of it: P is then at most 2^kTau, numerator and denominator share the
+// reference, so the result is the same ratio, and the accumulator rescale (one multiply per
+// accumulator register) almost never runs. The test needs no row maximum: a lane's row sum over
+// the 32 keys it owns in a tile exceeds kSumTrigger only if one of them exceeds 2^kTau (an
+// overflowed or NaN sum fails the comparison too), and the sum is needed anyway.
 constexpr float kTau = 8.0f;
+constexpr float kSumTrigger = 32.0f * 256.0f;   // 32 keys per lane and tile, each at most 2^kTau
 
 template <int D, int BR, int KRED, bool DISTR, int NG>
 __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
@@ -275,6 +279,11 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
   // exactly (8 vs 11 significand bits) inside half's exponent range, and the fused keys, rounded
   // to half from the sum of such values, keep 3 more bits than bf16 would: with bf16 K_f the logit error
   // on inputs with heavy-tailed channel scales exceeds what the output tolerance allows.
+  // distr: Q_r carries the factor softmax_scale * log2(e), rounded once more to half (11 bits:
+  // the rounding is 8 times finer than the bf16 grid the inputs come from). The score
+  // accumulators then hold the exponent of 2 directly. The exact path keeps Q as it is: scaling
+  // and re-rounding to bf16 would cost accuracy on rows with close top scores, so there the
+  // factor is applied to the float scores, one fused multiply-add per score.
   kx8 qop[C::KSTEPS];
   if constexpr (DISTR) {
     const bf16* qrow = qh + (size_t)q_ld * D;
@@ -283,7 +292,7 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
 #pragma unroll
       for (int j = 0; j < 8; ++j)
         if (NG == KRED || 16 * s + 8 * hh + j < NG)
-          qop[s][j] = to_half_sat((float)qrow[perm_lds[(16 * s + 8 * hh + j) * C::G]]);
+          qop[s][j] = to_half_sat((float)qrow[perm_lds[(16 * s + 8 * hh + j) * C::G]] * scale_log2e);
         else
           qop[s][j] = (f16)0.0f;   // padding of the contraction: no group there
     }
@@ -395,8 +404,16 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
   for (int mb = 0; mb < D / 32; ++mb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) oacc[mb][i] = 0.0f;
-  float m_ref = -INFINITY;   // reference row max, log2 units (scaled); at most kTau below the true max
-  float l_run = 0.0f;        // row sum over this lane's half of the keys, relative to m_ref
+  // Softmax state of this lane's query row, in the exp2 domain: the negated reference maximum
+  // and the row sum relative to it. distr: the negated reference also sits in all 16 registers
+  // of neg_ref, which the first MFMA of every score chain takes as its addend, so the
+  // accumulators come out as (scaled score - m_ref) and go straight into exp2.
+  constexpr bool PRESCALED = DISTR;
+  float nref = 0.0f;
+  f32x16 neg_ref;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) neg_ref[i] = 0.0f;
+  float l_run = 0.0f;        // over this lane's half of the keys
 
   // LDS byte offsets of this lane's operands inside a buffer.
   // Score product, A operand (exact): row lq (+32 per key block), logical chunk 2*s + hh.
@@ -434,8 +451,6 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[mb][i] = 0.0f;
-#pragma unroll
       for (int s = 0; s < C::KSTEPS; ++s) {
         kx8 a;
         if constexpr (DISTR)
@@ -443,38 +458,80 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
                                     base + ka_off[mb * 2 + 1] + s * 16 * C::KTROWB);
         else
           a = *(const kx8*)(base + ka_off[s] + mb * 32 * C::ROWB);
+        if (s == 0) {
+          if constexpr (PRESCALED) sacc[mb] = neg_ref;
+          else
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sacc[mb][i] = 0.0f;
+        }
         sacc[mb] = mfma_32x32x16(a, qop[s], sacc[mb]);
       }
     }
   };
 
-  // Softmax bookkeeping for the scores `sc` of tile `tile`, before they are exponentiated: mask,
-  // row maximum, and -- only when some row's maximum ran more than kTau ahead of its reference --
-  // a new reference with the matching rescale of the row sum and of the output accumulator.
-  auto row_max = [&](auto mask_c, int tile, f32x16 (&sc)[2]) -> float {
-    if constexpr (decltype(mask_c)::value) {
-      const int lim = causal ? min(q_abs, N - 1) : N - 1;  // last visible key of this row
+  // Causal / ragged-tail mask of the scores of tile `tile`.
+  auto apply_mask = [&](int tile, f32x16 (&sc)[2]) {
+    const int lim = causal ? min(q_abs, N - 1) : N - 1;  // last visible key of this row
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          int kv = tile * kBc + 32 * mb + 8 * (i >> 2) + 4 * hh + (i & 3);
-          if (kv > lim) sc[mb][i] = -INFINITY;
-        }
-    }
+      for (int i = 0; i < 16; ++i) {
+        int kv = tile * kBc + 32 * mb + 8 * (i >> 2) + 4 * hh + (i & 3);
+        if (kv > lim) sc[mb][i] = -INFINITY;
+      }
+  };
+  // Row maximum of a tile's scores (relative to the current reference), the same in both lanes
+  // of a row.
+  auto tile_max = [&](const f32x16 (&sc)[2]) -> float {
     float mt = sc[0][0];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sc[mb][i]);
-    return half_swap_max(mt) * scale_log2e;
+    mt = half_swap_max(mt);
+    return PRESCALED ? mt : __builtin_fmaf(mt, scale_log2e, nref);
   };
-  auto move_reference = [&](float mt) {
-    const bool moved = mt > m_ref + kTau;
-    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
-      const float m_new = moved ? mt : m_ref;
-      const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // exp2(-inf) = 0 on the first tile
-      m_ref = m_new;
+  // P = exp2(scores) rounded to bf16, as the B operands of P.V; returns this lane's row sum. The
+  // sum is taken over the rounded P, the values P.V really uses (one bf16 dot product with (1, 1)
+  // per register pair): numerator and denominator then carry the same rounding, which cancels
+  // for rows dominated by few keys.
+  auto exp_tile = [&](const f32x16 (&sc)[2], bf16x8 (&pop)[4]) -> float {
+    const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
+    float rs0 = 0.0f, rs1 = 0.0f;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        float x0 = sc[mb][i], x1 = sc[mb][i + 1];
+        if constexpr (!PRESCALED) {
+          x0 = __builtin_fmaf(x0, scale_log2e, nref);
+          x1 = __builtin_fmaf(x1, scale_log2e, nref);
+        }
+        bf16x2 pr = {(bf16)__builtin_amdgcn_exp2f(x0), (bf16)__builtin_amdgcn_exp2f(x1)};
+        pop[mb * 2 + (i >> 3)][i & 7] = pr[0];
+        pop[mb * 2 + (i >> 3)][(i & 7) + 1] = pr[1];
+        if (i & 2) rs1 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs1, false);
+        else rs0 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs0, false);
+      }
+    return rs0 + rs1;
+  };
+  // The reference of this lane's row moves up by `delta`: everything that is relative to it
+  // follows (row sum, output accumulator, the scores already computed against the old one).
+  auto shift_reference = [&](float delta, auto rescale_c, f32x16 (&sc)[2], auto next_c, f32x16 (&sn)[2]) {
+    nref -= delta;
+    if constexpr (PRESCALED) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) neg_ref[i] -= delta;
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          sc[mb][i] -= delta;
+          if constexpr (decltype(next_c)::value) sn[mb][i] -= delta;
+        }
+    }
+    if constexpr (decltype(rescale_c)::value) {
+      const float alpha = __builtin_amdgcn_exp2f(-delta);
       l_run *= alpha;
 #pragma unroll
       for (int mb = 0; mb < D / 32; ++mb)
@@ -483,10 +540,10 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
     }
   };
 
-  // One tile `it`, whose scores `sc` already went through row_max / move_reference:
-  //   phase X: scores of tile it+1 into `sn` (matrix pipe)  ||  exp, bf16 P, row sum of `sc` (vector ALUs)
-  //   phase Y: O^T += V^T . P^T for tile it (matrix pipe)    ||  mask and row maximum of `sn` (vector ALUs)
-  // then the rare reference move for tile it+1, the LDS stores of the prefetched tiles, one barrier.
+  // One tile `it`, whose scores `sc` are masked and relative to the row's reference:
+  //   scores of tile it+1 into `sn` (matrix pipe)  ||  exp2, bf16 P, row sum of `sc` (vector ALUs)
+  //   the rare reference move, then O^T += V^T . P^T for tile it (matrix pipe), the mask of
+  //   tile it+1 where it needs one, one barrier.
   auto body = [&](auto mask_next_c, auto next_c, int it, int par, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
     constexpr bool HAS_NEXT = decltype(next_c)::value;
     // The buffers these loads fill were last read in the previous iteration, which every wave
@@ -503,27 +560,16 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
       dma_tile(v_rsrc, it + 1, dma_v, v_buf(par ^ 1));
     }
     if constexpr (HAS_NEXT) qk(par ^ 1, sn);
-    // The row sum is taken over the bf16-rounded P, the values P.V really uses (one bf16 dot
-    // product with (1, 1) per register pair): numerator and denominator then carry the same
-    // rounding, which cancels for rows dominated by few keys.
     bf16x8 pop[4];
-    {
-      const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
-      float rs0 = 0.0f, rs1 = 0.0f;
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-          float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mb][i], scale_log2e, -m_ref));
-          float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mb][i + 1], scale_log2e, -m_ref));
-          bf16x2 pr = {(bf16)p0, (bf16)p1};
-          pop[mb * 2 + (i >> 3)][i & 7] = pr[0];
-          pop[mb * 2 + (i >> 3)][(i & 7) + 1] = pr[1];
-          if (i & 2) rs1 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs1, false);
-          else rs0 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs0, false);
-        }
-      l_run += rs0 + rs1;
+    float rs = exp_tile(sc, pop);
+    if (__builtin_amdgcn_ballot_w64(!(rs <= kSumTrigger)) != 0) {
+      // Some row of this wave met a score more than kTau above its reference: such rows take the
+      // tile's maximum as their new reference and the tile's P is computed again.
+      const float mt = tile_max(sc);
+      shift_reference(mt > kTau ? mt : 0.0f, std::true_type(), sc, next_c, sn);
+      rs = exp_tile(sc, pop);
     }
+    l_run += rs;
     // ---- O^T += V^T . P^T: step tt covers keys 16*tt + {8*(j/4) + 4*hh + j%4} of the tile,
     // i.e. V rows 16*tt + 4*hh + 0..3 and 16*tt + 8 + 4*hh + 0..3.
     const char* vb = v_buf(par);
@@ -536,10 +582,8 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
         oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pop[tt], oacc[mb], 0, 0, 0);
       }
     }
-    float mt_next = 0.0f;
-    if constexpr (HAS_NEXT) mt_next = row_max(mask_next_c, it + 1, sn);
     if constexpr (HAS_NEXT) {
-      move_reference(mt_next);
+      if constexpr (decltype(mask_next_c)::value) apply_mask(it + 1, sn);
       dma_wait();              // this wave's direct loads have landed
     }
     __syncthreads();
@@ -566,8 +610,11 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
   const std::true_type yes;
   const std::false_type no;
   f32x16 s0[2], s1[2];
-  qk(0, s0);
-  move_reference(row_max(yes, 0, s0));
+  qk(0, s0);             // against the initial reference 0
+  apply_mask(0, s0);
+  // The first tile sets the reference to its row maximum (key 0 is visible to every row, so the
+  // maximum is finite); nothing has been accumulated yet, so nothing is rescaled.
+  shift_reference(tile_max(s0), no, s0, no, s1);
   // The first iteration refills the buffer of tile 0 (direct load of K(2), or the fusion of
   // K_f^T(2)): every wave must have read its scores of tile 0 out of it first.
   __syncthreads();

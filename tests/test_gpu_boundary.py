@@ -64,9 +64,10 @@ def test_caller_grouping_table(base, kw):
 
 
 def test_half_range_clamp_of_the_reduced_product():
-    """bf16 DistrAttention holds Q_r and K_f in half precision: |q| beyond 65504 and |k| beyond
-    65504 / G* are clamped (documented input limit). The oracle, fed the clamped values and the
-    grouping of the unclamped Q (the LSH stage sees the original values), must agree."""
+    """bf16 DistrAttention holds Q_r (times softmax_scale * log2 e) and K_f in half precision:
+    |q| * softmax_scale * log2(e) beyond 65504 and |k| beyond 65504 / G* are clamped (documented
+    input limit). The oracle, fed the clamped values and the grouping of the unclamped Q (the
+    LSH stage sees the original values), must agree."""
     import gpu_util as U
     for n_groups in (32, 16):
         cfg = small("vit", B=1, H=2, Hkv=2, N=150, n_groups=n_groups)
@@ -78,7 +79,9 @@ def test_half_range_clamp_of_the_reduced_product():
         k[0, 0, 10, 7], k[0, 1, 100, 33], k[0, 0, 64, 0] = big, -big, -big
         p = U.oracle_params(cfg)
         perm = oracle.lsh_group(q, p)[1]
-        qc = np.clip(q, -65504.0, 65504.0).astype(np.float32)
+        q_lim = 65504.0 / (np.log2(np.e) / np.sqrt(cfg.d))
+        assert float(big) > q_lim
+        qc = np.clip(q, -q_lim, q_lim).astype(np.float32)
         kc = np.clip(k, -65504.0 / G, 65504.0 / G).astype(np.float32)
         print(f"case {cfg} clamp", flush=True)
         o_gpu, perm_gpu, _ = U.run_gpu(cfg, q, k, v, distr=True, want_tables=True)
