@@ -20,6 +20,7 @@ class OracleParams(ctypes.Structure):
         ("d", ctypes.c_int), ("Br", ctypes.c_int), ("n_groups", ctypes.c_int),
         ("causal", ctypes.c_int), ("n_planes", ctypes.c_int), ("gray_mode", ctypes.c_int),
         ("lsh_seed", ctypes.c_uint64), ("scale", ctypes.c_double),
+        ("Nk", ctypes.c_int), ("side", ctypes.c_int), ("Bc", ctypes.c_int),
     ]
 
 
@@ -45,11 +46,17 @@ def _ptr(a, ctype):
 
 
 def params(B, H, Hkv, N, d, Br, n_groups, causal=False, n_planes=16, gray_mode=0, lsh_seed=0,
-           scale=None):
+           scale=None, Nk=None, side=0, Bc=64):
+    """Nk: keys per head (default N); side 1: the mirrored form (sample K, fuse Q, one grouping
+    per K block of Bc rows)."""
     if scale is None:
         scale = 1.0 / np.sqrt(d)
     return OracleParams(B, H, Hkv, N, d, Br, n_groups, int(bool(causal)), n_planes, gray_mode,
-                        lsh_seed, float(scale))
+                        lsh_seed, float(scale), 0 if Nk is None else Nk, side, Bc)
+
+
+def n_keys(p):
+    return p.Nk if p.Nk > 0 else p.N
 
 
 def _check(rc, name):
@@ -156,7 +163,7 @@ def distr_fwd_tiles(q, k, v, p, tiles, R=None, perm=None):
 
 
 def scores(q, k, p, b=0, h=0, R=None, perm=None, want_exact=True, want_hat=True):
-    """-> (s_hat [N,N] or None, s [N,N] or None): scaled, unmasked score matrices of one head."""
+    """-> (s_hat [N,Nk] or None, s [N,Nk] or None): scaled, unmasked score matrices of one head."""
     q, qp = _f32(q)
     k, kp = _f32(k)
     Rp = None
@@ -164,8 +171,8 @@ def scores(q, k, p, b=0, h=0, R=None, perm=None, want_exact=True, want_hat=True)
         R, Rp = _f32(R)
     if perm is not None:
         perm = np.ascontiguousarray(perm, dtype=np.uint8)
-    s_hat = np.zeros((p.N, p.N), dtype=np.float64) if want_hat else None
-    s = np.zeros((p.N, p.N), dtype=np.float64) if want_exact else None
+    s_hat = np.zeros((p.N, n_keys(p)), dtype=np.float64) if want_hat else None
+    s = np.zeros((p.N, n_keys(p)), dtype=np.float64) if want_exact else None
     _check(lib().oracle_scores(qp, kp, _ptr(s_hat, ctypes.c_double), _ptr(s, ctypes.c_double),
                                ctypes.byref(p), Rp, _ptr(perm, ctypes.c_uint8), b, h),
            "oracle_scores")

@@ -16,6 +16,10 @@
  *   Sec. 3.3: all of the above once per Q block, the block's grouping applied to
  *            every key;
  *   Sec. 2.1: P = softmax(S^) row-wise, O = P V with the full V.
+ * The mirrored form (Sec. 3.1 last sentence of the Eq. 2 paragraph, Fig. 4 right side,
+ * Sec. 3.3 "(sum q_i) k^T"): the same steps with the roles of Q and K^T exchanged -- the
+ * grouping comes from the channel columns of a K block, one K column per group is sampled and
+ * the group's Q columns are summed.
  */
 #include "distr_attn_oracle.h"
 
@@ -34,10 +38,13 @@ int oracle_num_threads(void) {
 #endif
 }
 
+static int n_keys_of(const oracle_params *p) { return p->Nk > 0 ? p->Nk : p->N; }
+
 static int check_params(const oracle_params *p) {
   if (!p) return -1;
-  if (p->B <= 0 || p->H <= 0 || p->Hkv <= 0 || p->N <= 0 || p->d <= 0) return -1;
+  if (p->B <= 0 || p->H <= 0 || p->Hkv <= 0 || p->N <= 0 || p->d <= 0 || p->Nk < 0) return -1;
   if (p->H % p->Hkv != 0) return -1;
+  if (p->causal && n_keys_of(p) < p->N) return -1; /* the first queries would see no key */
   return 0;
 }
 
@@ -47,6 +54,8 @@ static int check_distr_params(const oracle_params *p) {
   if (p->d > 256) return -1; /* perm entries are bytes */
   if (p->n_planes < 1 || p->n_planes > 32) return -1;
   if (p->gray_mode != 0 && p->gray_mode != 1) return -1;
+  if (p->side != 0 && p->side != 1) return -1;
+  if (p->side == 1 && p->Bc <= 0) return -1;
   return 0;
 }
 
@@ -173,11 +182,11 @@ static void softmax_pv(double *s, int n_vis, const float *vh, int d, double *out
 }
 
 /* Exact attention for rows r0..r0+rows-1 of one head. */
-static void exact_block(const float *qh, const float *kh, const float *vh, int N, int d, int r0,
-                        int rows, int causal, double scale, double *o_rows, double *s) {
+static void exact_block(const float *qh, const float *kh, const float *vh, int Nk, int shift, int d,
+                        int r0, int rows, int causal, double scale, double *o_rows, double *s) {
   for (int r = 0; r < rows; ++r) {
     int i = r0 + r;
-    int n_vis = causal ? i + 1 : N;
+    int n_vis = causal ? i + shift + 1 : Nk; /* shift = Nk - N: last query sees every key */
     const float *qi = qh + (size_t)i * d;
     for (int n = 0; n < n_vis; ++n) {
       const float *kn = kh + (size_t)n * d;
@@ -205,15 +214,15 @@ static void fuse_keys(const float *kh, int n_keys, int d, const uint8_t *perm, i
 }
 
 /* DistrAttention for one Q block given its permutation. kf and s are scratch. */
-static void distr_block(const float *qh, const float *kh, const float *vh, int N, int d, int r0,
-                        int rows, int causal, double scale, const uint8_t *perm, int n_groups,
-                        double *o_rows, double *kf, double *s) {
+static void distr_block(const float *qh, const float *kh, const float *vh, int Nk, int shift, int d,
+                        int r0, int rows, int causal, double scale, const uint8_t *perm,
+                        int n_groups, double *o_rows, double *kf, double *s) {
   const int G = d / n_groups;
-  int n_keys = causal ? r0 + rows : N; /* keys any row of the block can see */
+  int n_keys = causal ? r0 + rows + shift : Nk; /* keys any row of the block can see */
   fuse_keys(kh, n_keys, d, perm, n_groups, kf);
   for (int r = 0; r < rows; ++r) {
     int i = r0 + r;
-    int n_vis = causal ? i + 1 : N;
+    int n_vis = causal ? i + shift + 1 : Nk;
     const float *qi = qh + (size_t)i * d;
     for (int n = 0; n < n_vis; ++n) {
       const double *kfn = kf + (size_t)n * n_groups;
@@ -226,21 +235,67 @@ static void distr_block(const float *qh, const float *kh, const float *vh, int N
   }
 }
 
+/* The mirrored form for one Q block: for every K block (Bc rows) its own grouping
+ * perm_k[tb] (from that K block's channel columns); S^[i][n] = scale * sum_j
+ * (sum_{g} Q[i][member g of group j]) * K[n][first member of group j]  for n in block tb.
+ * qf is scratch of n_groups doubles. */
+static void distr_block_kside(const float *qh, const float *kh, const float *vh, int Nk, int shift,
+                              int d, int r0, int rows, int causal, double scale,
+                              const uint8_t *perm_k, int Bc, int n_groups, double *o_rows,
+                              double *qf, double *s) {
+  const int G = d / n_groups;
+  for (int r = 0; r < rows; ++r) {
+    int i = r0 + r;
+    int n_vis = causal ? i + shift + 1 : Nk;
+    const float *qi = qh + (size_t)i * d;
+    for (int n0 = 0; n0 < n_vis; n0 += Bc) {
+      const uint8_t *perm = perm_k + (size_t)(n0 / Bc) * d;
+      for (int j = 0; j < n_groups; ++j) { /* fusion of the query's channels, in sorted order */
+        double acc = 0.0;
+        for (int g = 0; g < G; ++g) acc += (double)qi[perm[j * G + g]];
+        qf[j] = acc;
+      }
+      int n1 = n0 + Bc < n_vis ? n0 + Bc : n_vis;
+      for (int n = n0; n < n1; ++n) {
+        const float *kn = kh + (size_t)n * d;
+        double acc = 0.0;
+        for (int j = 0; j < n_groups; ++j) /* sampling: the group's first K column in sorted order */
+          acc += qf[j] * (double)kn[perm[j * G]];
+        s[n] = scale * acc;
+      }
+    }
+    softmax_pv(s, n_vis, vh, d, o_rows + (size_t)r * d);
+  }
+}
+
+/* Groupings of every K block of one kv head: perm_k[tb][d]. */
+static void lsh_key_blocks(const float *kh, int Nk, int d, const float *R, int Bc, int n_planes,
+                           int gray_mode, uint8_t *perm_k) {
+  for (int n0 = 0; n0 < Nk; n0 += Bc) {
+    uint32_t hash[256];
+    int rows = Nk - n0 < Bc ? Nk - n0 : Bc;
+    lsh_block(kh, d, n0, rows, R, Bc, n_planes, gray_mode, hash, perm_k + (size_t)(n0 / Bc) * d, NULL);
+  }
+}
+
 static int run_tiles(const float *q, const float *k, const float *v, double *o,
                      const oracle_params *p, const float *R, const uint8_t *perm_in,
                      const int *tiles, long n_units, int distr, int packed_out) {
   if (!q || !k || !v || !o) return -1;
   if (distr ? check_distr_params(p) : check_params(p)) return -1;
   if (!distr && p->Br <= 0 && tiles) return -1;
-  const int N = p->N, d = p->d;
+  const int N = p->N, d = p->d, Nk = n_keys_of(p), shift = Nk - N;
   const int Br = (p->Br > 0) ? p->Br : N;
   const int Tq = (N + Br - 1) / Br;
   const int rep = p->H / p->Hkv;
+  const int kside = distr && p->side == 1;
+  const int Tk = kside ? (Nk + p->Bc - 1) / p->Bc : 0;
+  const int lsh_rows = kside ? p->Bc : Br; /* rows of the blocks the LSH runs on */
   float *Rown = NULL;
   if (distr && !perm_in && !R) {
-    Rown = (float *)malloc(sizeof(float) * (size_t)p->n_planes * Br);
+    Rown = (float *)malloc(sizeof(float) * (size_t)p->n_planes * lsh_rows);
     if (!Rown) return -2;
-    oracle_hyperplanes(p->lsh_seed, p->n_planes, Br, Rown);
+    oracle_hyperplanes(p->lsh_seed, p->n_planes, lsh_rows, Rown);
     R = Rown;
   }
   if (tiles) {
@@ -255,9 +310,11 @@ static int run_tiles(const float *q, const float *k, const float *v, double *o,
   int failed = 0;
 #pragma omp parallel
   {
-    double *s = (double *)malloc(sizeof(double) * (size_t)N);
-    double *kf = distr ? (double *)malloc(sizeof(double) * (size_t)N * p->n_groups) : NULL;
-    if (!s || (distr && !kf)) {
+    double *s = (double *)malloc(sizeof(double) * (size_t)Nk);
+    double *kf = (distr && !kside) ? (double *)malloc(sizeof(double) * (size_t)Nk * p->n_groups) : NULL;
+    double *qf = kside ? (double *)malloc(sizeof(double) * (size_t)p->n_groups) : NULL;
+    uint8_t *perm_k = kside ? (uint8_t *)malloc((size_t)Tk * d) : NULL;
+    if (!s || (distr && !kside && !kf) || (kside && (!qf || !perm_k))) {
 #pragma omp atomic write
       failed = 1;
     }
@@ -276,14 +333,20 @@ static int run_tiles(const float *q, const float *k, const float *v, double *o,
           b = (int)(u / ((long)Tq * p->H));
         }
         const float *qh = q + ((size_t)b * p->H + h) * N * d;
-        const float *kh = k + ((size_t)b * p->Hkv + h / rep) * N * d;
-        const float *vh = v + ((size_t)b * p->Hkv + h / rep) * N * d;
+        const float *kh = k + ((size_t)b * p->Hkv + h / rep) * Nk * d;
+        const float *vh = v + ((size_t)b * p->Hkv + h / rep) * Nk * d;
         int r0 = t * Br;
         int rows = N - r0 < Br ? N - r0 : Br;
         double *o_rows = packed_out ? o + (size_t)u * Br * d
                                     : o + (((size_t)b * p->H + h) * N + r0) * d;
         if (!distr) {
-          exact_block(qh, kh, vh, N, d, r0, rows, p->causal, p->scale, o_rows, s);
+          exact_block(qh, kh, vh, Nk, shift, d, r0, rows, p->causal, p->scale, o_rows, s);
+        } else if (kside) {
+          const uint8_t *pk = perm_k;
+          if (perm_in) pk = perm_in + ((size_t)b * p->Hkv + h / rep) * Tk * d;
+          else lsh_key_blocks(kh, Nk, d, R, p->Bc, p->n_planes, p->gray_mode, perm_k);
+          distr_block_kside(qh, kh, vh, Nk, shift, d, r0, rows, p->causal, p->scale, pk, p->Bc,
+                            p->n_groups, o_rows, qf, s);
         } else {
           uint8_t perm[256];
           size_t unit = ((size_t)b * p->H + h) * Tq + t;
@@ -293,13 +356,15 @@ static int run_tiles(const float *q, const float *k, const float *v, double *o,
             uint32_t hash[256];
             lsh_block(qh, d, r0, rows, R, Br, p->n_planes, p->gray_mode, hash, perm, NULL);
           }
-          distr_block(qh, kh, vh, N, d, r0, rows, p->causal, p->scale, perm, p->n_groups, o_rows,
-                      kf, s);
+          distr_block(qh, kh, vh, Nk, shift, d, r0, rows, p->causal, p->scale, perm, p->n_groups,
+                      o_rows, kf, s);
         }
       }
     }
     free(s);
     free(kf);
+    free(qf);
+    free(perm_k);
   }
   free(Rown);
   return failed ? -2 : 0;
@@ -337,28 +402,51 @@ int oracle_scores(const float *q, const float *k, double *s_hat, double *s,
                   const oracle_params *p, const float *R, const uint8_t *perm_in, int b, int h) {
   if (!q || !k || check_distr_params(p)) return -1;
   if (b < 0 || b >= p->B || h < 0 || h >= p->H) return -1;
-  const int N = p->N, d = p->d, Br = p->Br, G = d / p->n_groups;
+  const int N = p->N, d = p->d, Br = p->Br, G = d / p->n_groups, Nk = n_keys_of(p);
   const int Tq = (N + Br - 1) / Br;
   const int rep = p->H / p->Hkv;
+  const int kside = p->side == 1;
+  const int lsh_rows = kside ? p->Bc : Br;
   const float *qh = q + ((size_t)b * p->H + h) * N * d;
-  const float *kh = k + ((size_t)b * p->Hkv + h / rep) * N * d;
+  const float *kh = k + ((size_t)b * p->Hkv + h / rep) * Nk * d;
   float *Rown = NULL;
   if (s_hat && !perm_in && !R) {
-    Rown = (float *)malloc(sizeof(float) * (size_t)p->n_planes * Br);
+    Rown = (float *)malloc(sizeof(float) * (size_t)p->n_planes * lsh_rows);
     if (!Rown) return -2;
-    oracle_hyperplanes(p->lsh_seed, p->n_planes, Br, Rown);
+    oracle_hyperplanes(p->lsh_seed, p->n_planes, lsh_rows, Rown);
     R = Rown;
   }
   if (s) {
     for (int i = 0; i < N; ++i)
-      for (int n = 0; n < N; ++n) {
+      for (int n = 0; n < Nk; ++n) {
         double acc = 0.0;
         for (int c = 0; c < d; ++c) acc += (double)qh[(size_t)i * d + c] * (double)kh[(size_t)n * d + c];
-        s[(size_t)i * N + n] = p->scale * acc;
+        s[(size_t)i * Nk + n] = p->scale * acc;
       }
   }
-  if (s_hat) {
-    double *kf = (double *)malloc(sizeof(double) * (size_t)N * p->n_groups);
+  if (s_hat && kside) {
+    const int Tk = (Nk + p->Bc - 1) / p->Bc;
+    uint8_t *perm_k = (uint8_t *)malloc((size_t)Tk * d);
+    if (!perm_k) {
+      free(Rown);
+      return -2;
+    }
+    if (perm_in) memcpy(perm_k, perm_in + ((size_t)b * p->Hkv + h / rep) * Tk * d, (size_t)Tk * d);
+    else lsh_key_blocks(kh, Nk, d, R, p->Bc, p->n_planes, p->gray_mode, perm_k);
+    for (int i = 0; i < N; ++i)
+      for (int n = 0; n < Nk; ++n) {
+        const uint8_t *perm = perm_k + (size_t)(n / p->Bc) * d;
+        double acc = 0.0;
+        for (int j = 0; j < p->n_groups; ++j) {
+          double qsum = 0.0;
+          for (int g = 0; g < G; ++g) qsum += (double)qh[(size_t)i * d + perm[j * G + g]];
+          acc += qsum * (double)kh[(size_t)n * d + perm[j * G]];
+        }
+        s_hat[(size_t)i * Nk + n] = p->scale * acc;
+      }
+    free(perm_k);
+  } else if (s_hat) {
+    double *kf = (double *)malloc(sizeof(double) * (size_t)Nk * p->n_groups);
     if (!kf) {
       free(Rown);
       return -2;
@@ -373,14 +461,14 @@ int oracle_scores(const float *q, const float *k, double *s_hat, double *s,
         uint32_t hash[256];
         lsh_block(qh, d, r0, rows, R, Br, p->n_planes, p->gray_mode, hash, perm, NULL);
       }
-      fuse_keys(kh, N, d, perm, p->n_groups, kf);
+      fuse_keys(kh, Nk, d, perm, p->n_groups, kf);
       for (int r = 0; r < rows; ++r) {
         int i = r0 + r;
-        for (int n = 0; n < N; ++n) {
+        for (int n = 0; n < Nk; ++n) {
           double acc = 0.0;
           for (int j = 0; j < p->n_groups; ++j)
             acc += (double)qh[(size_t)i * d + perm[j * G]] * kf[(size_t)n * p->n_groups + j];
-          s_hat[(size_t)i * N + n] = p->scale * acc;
+          s_hat[(size_t)i * Nk + n] = p->scale * acc;
         }
       }
     }

@@ -11,7 +11,7 @@
  * tests, the smoke check and the benchmark's cpu_baseline leg.
  *
  * All pointers are host pointers. q and o are [B][H][N][d], k and v are
- * [B][Hkv][N][d], contiguous, d fastest. Inputs are float (bf16 workloads
+ * [B][Hkv][Nk][d] (Nk = N unless oracle_params.Nk says otherwise), contiguous, d fastest. Inputs are float (bf16 workloads
  * pass bf16-representable floats), every dot product, sum and softmax is
  * taken in double, outputs are double. The one exception is the LSH
  * projection, whose sign decides an integer: it is taken in float with one
@@ -38,6 +38,14 @@ typedef struct {
   int gray_mode;  /* 0: hash = rank of the sign word read as a Gray codeword; 1: hash = sign word Gray-encoded */
   uint64_t lsh_seed;
   double scale;   /* multiplies S before softmax */
+  int Nk;         /* number of keys / values per head; 0 means N. With causal != 0 (needs Nk >= N)
+                     the last query is aligned with the last key: key n is visible to query i
+                     iff n <= i + (Nk - N) */
+  int side;       /* 0: sample Q columns, fuse K columns, one grouping per Q block of Br rows
+                        (the form the paper builds, Sec. 3.2-3.3);
+                     1: the mirrored form of Sec. 3.1 / Fig. 4 right: sample K columns, fuse Q
+                        columns, one grouping per K block of Bc rows, taken from that K block */
+  int Bc;         /* rows of a K block; only side 1 depends on it */
 } oracle_params;
 
 /* Projection matrix R[n_planes][Br] from the seed (counter-based, exactly representable floats). */
@@ -61,7 +69,8 @@ int oracle_exact_fwd(const float *q, const float *k, const float *v, double *o,
                      const oracle_params *p);
 
 /* DistrAttention, all rows. R may be NULL (then it comes from p->lsh_seed).
- * perm (may be NULL) overrides the LSH grouping: [B][H][Tq][d]. */
+ * perm (may be NULL) overrides the LSH grouping: [B][H][Tq][d] (side 1: [B][Hkv][Tk][d], and R is
+ * [n_planes][Bc]). */
 int oracle_distr_fwd(const float *q, const float *k, const float *v, double *o,
                      const oracle_params *p, const float *R, const uint8_t *perm);
 
@@ -73,8 +82,9 @@ int oracle_distr_fwd_tiles(const float *q, const float *k, const float *v, doubl
                            const oracle_params *p, const float *R, const uint8_t *perm,
                            const int *tiles, int n_tiles);
 
-/* Unnormalised score blocks for one (b, h): s_hat and s are [N][N] doubles
- * (scale applied, no mask). Either may be NULL. */
+/* Unnormalised score blocks for one (b, h): s_hat and s are [N][Nk] doubles
+ * (scale applied, no mask). Either may be NULL. For side 1, R is [n_planes][Bc] and perm is the
+ * table of the K blocks, [B][Hkv][ceil(Nk/Bc)][d]. */
 int oracle_scores(const float *q, const float *k, double *s_hat, double *s,
                   const oracle_params *p, const float *R, const uint8_t *perm, int b, int h);
 

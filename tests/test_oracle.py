@@ -327,6 +327,161 @@ def test_permutation_tables_are_valid_and_sorted():
 
 
 # --------------------------------------------------------------------------- Sec. 4.2 statistics (soft)
+# --------------------------------------------------------------------------- N_q != N_k
+def _sdpa_rect(q, k, v, causal, scale):
+    """torch's attention in float64 with an explicit mask: the last query is aligned with the last key."""
+    tq, tk, tv = (torch.from_numpy(np.asarray(x, dtype=np.float64)) for x in (q, k, v))
+    rep = tq.shape[1] // tk.shape[1]
+    tk, tv = tk.repeat_interleave(rep, dim=1), tv.repeat_interleave(rep, dim=1)
+    Nq, Nk = tq.shape[2], tk.shape[2]
+    mask = None
+    if causal:
+        mask = torch.arange(Nk)[None, :] <= torch.arange(Nq)[:, None] + (Nk - Nq)
+    return torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask, scale=scale).numpy()
+
+
+@pytest.mark.parametrize("B,H,Hkv,Nq,Nk,d,causal", [
+    (1, 1, 1, 1, 37, 8, False), (1, 1, 1, 1, 37, 8, True), (2, 4, 2, 20, 50, 16, True),
+    (1, 6, 3, 64, 33, 32, False), (1, 2, 1, 7, 7, 4, True), (1, 8, 2, 30, 129, 64, True)])
+def test_exact_with_other_key_count_matches_library_attention(B, H, Hkv, Nq, Nk, d, causal):
+    # Sec. 2.1 with Q of N_q rows and K, V of N_k rows (decode against a cache, cross attention);
+    # the paper never masks: the causal reading (last query sees every key) is this build's.
+    q, k, v = rand((B, H, Nq, d), 41), rand((B, Hkv, Nk, d), 42), rand((B, Hkv, Nk, d), 43)
+    p = oracle.params(B, H, Hkv, Nq, d, 16, d, causal=causal, scale=0.3, Nk=Nk)
+    np.testing.assert_allclose(oracle.exact_fwd(q, k, v, p), _sdpa_rect(q, k, v, causal, 0.3), rtol=0, atol=1e-12)
+    # groups of one channel: the approximation is the same product
+    np.testing.assert_allclose(oracle.distr_fwd(q, k, v, p), _sdpa_rect(q, k, v, causal, 0.3), rtol=0, atol=1e-12)
+
+
+def test_exact_with_other_key_count_scalar_loops():
+    Nq, Nk, d = 3, 5, 2
+    q, k, v = rand((1, 1, Nq, d), 44), rand((1, 1, Nk, d), 45), rand((1, 1, Nk, d), 46)
+    for causal in (False, True):
+        p = oracle.params(1, 1, 1, Nq, d, 2, d, causal=causal, scale=1.0, Nk=Nk)
+        o = oracle.exact_fwd(q, k, v, p)[0, 0]
+        for i in range(Nq):
+            vis = range(i + (Nk - Nq) + 1) if causal else range(Nk)
+            sc = {n: sum(float(q[0, 0, i, c]) * float(k[0, 0, n, c]) for c in range(d)) for n in vis}
+            z = sum(math.exp(x) for x in sc.values())
+            for c in range(d):
+                ref = sum(math.exp(sc[n]) / z * float(v[0, 0, n, c]) for n in vis)
+                assert abs(o[i, c] - ref) < 1e-12
+    with pytest.raises(ValueError):      # causal with fewer keys than queries: the first queries see nothing
+        oracle.exact_fwd(k, q, q, oracle.params(1, 1, 1, Nk, d, 2, d, causal=True, Nk=Nq))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_last_queries_of_a_square_problem(causal):
+    # Sec. 3.3: one grouping per Q block. When N_k - N_q is a multiple of Br the Q blocks of the
+    # N_q x N_k problem are the last Q blocks of the N_k x N_k problem, row for row, so exact and
+    # approximate outputs must be the corresponding rows of the square problem's.
+    B, H, Hkv, Nk, d, Br, G = 1, 4, 2, 100, 16, 16, 2
+    for Nq in (4, 36, 68):
+        qf, k, v = rand((B, H, Nk, d), 47), rand((B, Hkv, Nk, d), 48), rand((B, Hkv, Nk, d), 49)
+        q = np.ascontiguousarray(qf[:, :, Nk - Nq:])
+        sq = oracle.params(B, H, Hkv, Nk, d, Br, d // G, causal=causal, lsh_seed=5)
+        re = oracle.params(B, H, Hkv, Nq, d, Br, d // G, causal=causal, lsh_seed=5, Nk=Nk)
+        assert (Nk - Nq) % Br == 0
+        for fn in (oracle.exact_fwd, oracle.distr_fwd):
+            np.testing.assert_allclose(fn(q, k, v, re), fn(qf, k, v, sq)[:, :, Nk - Nq:], rtol=0, atol=1e-13)
+        assert np.array_equal(oracle.lsh_group(q, re)[1], oracle.lsh_group(qf, sq)[1][:, :, (Nk - Nq) // Br:])
+        s_hat_r, s_r = oracle.scores(q, k, re, h=3)
+        s_hat_s, s_s = oracle.scores(qf, k, sq, h=3)
+        np.testing.assert_allclose(s_hat_r, s_hat_s[Nk - Nq:], atol=1e-13)
+        np.testing.assert_allclose(s_r, s_s[Nk - Nq:], atol=1e-13)
+
+
+# --------------------------------------------------------------------------- mirrored form (sample K, fuse Q)
+def test_worked_example_fig4_right_side():
+    vals = {}
+    for line in open(os.path.join(GOLDEN, "fig4_kside.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        key, *nums = line.split()
+        vals[key] = [float(x) for x in nums]
+    q = np.array(vals["Q"], dtype=np.float32).reshape(1, 1, 2, 4)
+    k = np.array(vals["K"], dtype=np.float32).reshape(1, 1, 2, 4)
+    v = np.array(vals["V"], dtype=np.float32).reshape(1, 1, 2, 4)
+    perm = np.array(vals["PERM0"], dtype=np.uint8).reshape(1, 1, 1, 4)
+    p = oracle.params(1, 1, 1, 2, 4, 2, 2, scale=1.0, side=1, Bc=2)
+    s_hat, s = oracle.scores(q, k, p, perm=perm)
+    np.testing.assert_array_equal(s_hat.ravel(), vals["SHAT"])
+    np.testing.assert_array_equal(s.ravel(), vals["S"])
+    o = oracle.distr_fwd(q, k, v, p, perm=perm)[0, 0]
+    for i, gap in enumerate(vals["LOGIT_GAP"]):
+        expect = [1.0 / (1.0 + math.exp(gap)), math.exp(gap) / (1.0 + math.exp(gap)), 0.0, 0.0]
+        np.testing.assert_allclose(o[i], expect, atol=1e-15)
+
+
+def test_mirrored_form_is_the_transpose_of_the_form_with_roles_exchanged():
+    # Sec. 3.1: "the same operations applied on K^T". With one block on each side, the mirrored
+    # approximation of Q K^T is the transpose of the ordinary approximation of K Q^T: the grouping
+    # comes from the sampled operand in both.
+    N, d, G = 24, 16, 4
+    q, k = rand((1, 1, N, d), 50), rand((1, 1, N, d), 51)
+    for seed in (0, 9):
+        mirrored = oracle.params(1, 1, 1, N, d, N, d // G, scale=0.7, lsh_seed=seed, side=1, Bc=N)
+        ordinary = oracle.params(1, 1, 1, N, d, N, d // G, scale=0.7, lsh_seed=seed)
+        s_hat_m, s_m = oracle.scores(q, k, mirrored)
+        s_hat_o, s_o = oracle.scores(k, q, ordinary)
+        np.testing.assert_allclose(s_hat_m, s_hat_o.T, atol=1e-13)
+        np.testing.assert_allclose(s_m, s_o.T, atol=1e-13)
+        assert np.abs(s_hat_m - s_m).max() > 1e-3        # it is an approximation, not the product
+
+
+def test_mirrored_form_residual_identity_and_block_tables():
+    # S^ - S = sum_j sum_{i in G_j} q_i (k^_j - k_i)^T with the grouping of the K block the key
+    # belongs to (one grouping per K block of Bc rows, from that block's channel columns).
+    Nq, Nk, d, Bc, G = 21, 50, 12, 16, 3
+    q, k, v = rand((1, 2, Nq, d), 52), rand((1, 1, Nk, d), 53), rand((1, 1, Nk, d), 54)
+    p = oracle.params(1, 2, 1, Nq, d, 8, d // G, scale=1.0, lsh_seed=3, Nk=Nk, side=1, Bc=Bc)
+    # the K blocks' tables are what the LSH stage gives for K as its input with blocks of Bc rows
+    table = oracle.lsh_group(k, oracle.params(1, 1, 1, Nk, d, Bc, d // G, lsh_seed=3))[1]
+    q64, k64 = q[0, 1].astype(np.float64), k[0, 0].astype(np.float64)
+    s_hat, s = oracle.scores(q, k, p, h=1)
+    for tb in range((Nk + Bc - 1) // Bc):
+        cols = slice(tb * Bc, min(Nk, (tb + 1) * Bc))
+        resid = np.zeros((Nq, cols.stop - cols.start))
+        for j in range(d // G):
+            members = table[0, 0, tb, j * G:(j + 1) * G]
+            for i in members:
+                resid += np.outer(q64[:, i], k64[cols, members[0]] - k64[cols, i])
+        np.testing.assert_allclose(s_hat[:, cols] - s[:, cols], resid, atol=1e-12)
+    # a caller's table is honoured, and the forward is softmax(S^) V
+    np.testing.assert_allclose(oracle.scores(q, k, p, h=1, perm=table)[0], s_hat, atol=0)
+    for causal in (False, True):
+        pc = oracle.params(1, 2, 1, Nq, d, 8, d // G, scale=1.0, lsh_seed=3, Nk=Nk, side=1, Bc=Bc, causal=causal)
+        o = oracle.distr_fwd(q, k, v, pc)[0, 1]
+        logits = s_hat.copy()
+        if causal:
+            logits[np.arange(Nk)[None, :] > np.arange(Nq)[:, None] + (Nk - Nq)] = -np.inf
+        w = np.exp(logits - logits.max(1, keepdims=True))
+        np.testing.assert_allclose(o, (w / w.sum(1, keepdims=True)) @ v[0, 0].astype(np.float64), atol=1e-12)
+
+
+def test_mirrored_form_exact_cases():
+    B, H, Hkv, Nq, Nk, d = 1, 4, 2, 30, 45, 16
+    q, k, v = rand((B, H, Nq, d), 55), rand((B, Hkv, Nk, d), 56), rand((B, Hkv, Nk, d), 57)
+    # groups of one channel reproduce S (Sec. 3.1)
+    p1 = oracle.params(B, H, Hkv, Nq, d, 16, d, Nk=Nk, side=1, Bc=16, causal=True)
+    np.testing.assert_allclose(oracle.distr_fwd(q, k, v, p1), oracle.exact_fwd(q, k, v, p1), atol=1e-12)
+    # Eq. 1 mirrored: equal K columns inside every group make the approximation exact
+    G = 2
+    rng = np.random.default_rng(58)
+    place = rng.permutation(d)
+    kd = k.copy()
+    kd[..., place[1::2]] = kd[..., place[0::2]]
+    checked = 0
+    for seed in range(20):
+        p = oracle.params(B, H, Hkv, Nq, d, 16, d // G, Nk=Nk, side=1, Bc=16, lsh_seed=seed)
+        hashes = oracle.lsh_group(kd, oracle.params(B, Hkv, Hkv, Nk, d, 16, d // G, lsh_seed=seed))[0]
+        if not all(len(set(hashes[0, h, t].tolist())) == d // G for h in range(Hkv) for t in range(hashes.shape[2])):
+            continue
+        np.testing.assert_allclose(oracle.distr_fwd(q, kd, v, p), oracle.exact_fwd(q, kd, v, p), atol=1e-12)
+        checked += 1
+    assert checked >= 3
+
+
 def test_error_grows_with_group_size_as_in_table4():
     # Sec. 4.2, Table 4: U(0,1) entries, N = d = 64, block size 2, G* = 2, 4, 8, 16. The paper
     # prints mean relative errors 0.87, 1.73, 2.48, 4.96 %: each doubling of G* multiplies the

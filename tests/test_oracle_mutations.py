@@ -34,6 +34,14 @@ PIN_FUNCS = [
     pins.test_hyperplane_generator_statistics,
     pins.test_blocks_are_independent_and_single_block_is_global,
     pins.test_permutation_tables_are_valid_and_sorted,
+    lambda: [pins.test_exact_with_other_key_count_matches_library_attention(*a) for a in
+             [(1, 1, 1, 1, 37, 8, True), (2, 4, 2, 20, 50, 16, True), (1, 6, 3, 64, 33, 32, False)]],
+    pins.test_exact_with_other_key_count_scalar_loops,
+    lambda: [pins.test_last_queries_of_a_square_problem(c) for c in (False, True)],
+    pins.test_worked_example_fig4_right_side,
+    pins.test_mirrored_form_is_the_transpose_of_the_form_with_roles_exchanged,
+    pins.test_mirrored_form_residual_identity_and_block_tables,
+    pins.test_mirrored_form_exact_cases,
 ]
 
 # (name, text in the oracle source, replacement)
@@ -47,9 +55,16 @@ MUTANTS = [
     ("plane 0 in the lowest bit", "code |= bit << (n_planes - 1 - pl);", "code |= bit << pl;"),
     ("zero counts as positive", "(acc > 0.0f) ? 1u : 0u", "(acc >= 0.0f) ? 1u : 0u"),
     ("negative projections set the bit", "(acc > 0.0f) ? 1u : 0u", "(acc < 0.0f) ? 1u : 0u"),
-    ("causal mask off by one", "int n_vis = causal ? i + 1 : N;", "int n_vis = causal ? (i > 0 ? i : 1) : N;"),
+    ("causal mask off by one", "int n_vis = causal ? i + shift + 1 : Nk; /* shift", "int n_vis = causal ? (i + shift > 0 ? i + shift : 1) : Nk; /* shift"),
+    ("causal mask ignores the extra keys", "int n_vis = causal ? i + shift + 1 : Nk; /* shift", "int n_vis = causal ? i + 1 : Nk; /* shift"),
+    ("approximation's causal mask ignores the extra keys", "int n_keys = causal ? r0 + rows + shift : Nk;", "int n_keys = causal ? r0 + rows : Nk; shift = 0;"),
+    ("keys addressed with the query count", "const float *kh = k + ((size_t)b * p->Hkv + h / rep) * Nk * d;\n        const float *vh", "const float *kh = k + ((size_t)b * p->Hkv + h / rep) * N * d;\n        const float *vh"),
+    ("mirrored form samples the group's last key column", "acc += qf[j] * (double)kn[perm[j * G]];", "acc += qf[j] * (double)kn[perm[j * G + G - 1]];"),
+    ("mirrored form drops a query column from the fusion", "for (int g = 0; g < G; ++g) acc += (double)qi[perm[j * G + g]];", "for (int g = 0; g + 1 < G || g == 0; ++g) acc += (double)qi[perm[j * G + g]];"),
+    ("mirrored form uses the first K block's grouping everywhere", "const uint8_t *perm = perm_k + (size_t)(n0 / Bc) * d;", "const uint8_t *perm = perm_k;"),
+    ("mirrored form hashes the wrong rows of K", "lsh_block(kh, d, n0, rows, R, Bc,", "lsh_block(kh, d, 0, rows, R, Bc,"),
     ("scale applied twice", "s[n] = scale * acc;", "s[n] = scale * scale * acc;"),
-    ("GQA head mapping by modulo", "kh = k + ((size_t)b * p->Hkv + h / rep) * N * d;", "kh = k + ((size_t)b * p->Hkv + h % p->Hkv) * N * d;"),
+    ("GQA head mapping by modulo", "kh = k + ((size_t)b * p->Hkv + h / rep) * Nk * d;\n        const float *vh", "kh = k + ((size_t)b * p->Hkv + h % p->Hkv) * Nk * d;\n        const float *vh"),
     ("Gray rank replaced by Gray code", "for (uint32_t g = code; g; g >>= 1) rank ^= g;", "rank = code ^ (code >> 1);"),
     ("projection matrix read transposed", "R[(size_t)pl * Br + r], acc);", "R[(size_t)r * n_planes + pl], acc);"),
     ("projection walks the block's rows backwards", "R[(size_t)pl * Br + r], acc);", "R[(size_t)pl * Br + (rows - 1 - r)], acc);"),
