@@ -7,14 +7,17 @@
  * Conventions for every entry point
  *   - q, k, v, o and every pointer named *_out / workspace are DEVICE pointers owned by the
  *     caller; `const da_params*` and `float* host_out` are HOST pointers.
- *   - Layout: q and o are [B][H][N][d]; k and v are [B][Hkv][N][d]; contiguous, d fastest.
- *     Query head h reads key/value head h / (H / Hkv). Element type is bf16 or float (da_dtype).
+ *   - Layout: q and o are [B][H][N][d]; k and v are [B][Hkv][Nk][d] (Nk = N unless da_params.Nk
+ *     says otherwise); contiguous, d fastest. Query head h reads key/value head h / (H / Hkv).
+ *     Element type is bf16 or float (da_dtype).
  *   - q, k, v are never written. o must not alias an input. Base pointers must be 16-byte aligned.
- *   - Calls only enqueue work on the stream (asynchronous); they never synchronise the device.
+ *   - Calls only enqueue work on the stream (asynchronous); they never synchronise the device
+ *     (distr_attn_release does).
  *   - Return value: DA_OK or a negative da_status. All argument checks run on the host before
  *     anything is launched; on error nothing has been enqueued. distr_attn_last_error() gives a
  *     message for the last failure on the calling thread.
- *   - Notation: Tq = ceil(N / Br) query blocks; G* = d / n_groups channels per group.
+ *   - Notation: Tq = ceil(N / Br) query blocks; Tk = ceil(Nk / Bc) key blocks; G* = d / n_groups
+ *     channels per group.
  */
 #ifndef DISTR_ATTN_H
 #define DISTR_ATTN_H
@@ -43,8 +46,11 @@ typedef enum { DA_BF16 = 0, DA_F32 = 1 } da_dtype;
  * {4, 8, 16, 32, 64, 128} with G* = d / n_groups <= 16 (4 and 8 zero-pad the contraction to one MFMA
  * step of 16), for float any divisor of d; 1 <= n_planes <= 32;
  * N >= 1 arbitrary (ragged last blocks are masked), N * d * 4 < 2^31; at most 2^31 - 1 query blocks.
- * bf16 DistrAttention path: |q| and |k| beyond 65504 / G* are clamped (the reduced product runs in
- * half precision).
+ * bf16 DistrAttention path: the reduced product S^ = Q_r K_f^T runs in half precision on
+ * Q_r * softmax_scale * log2(e) and on K. Full precision needs magnitudes inside half's normal
+ * range: |q| * softmax_scale * log2(e) beyond 65504 and |k| beyond 65504 / G* are clamped; below
+ * 2^-14 (6.1e-5) values keep fewer significand bits (absolute step 2^-24) and below 2^-25 they
+ * become 0. The exact path and the float path have no such limit.
  */
 typedef struct {
   int B, H, Hkv, N, d;
@@ -61,8 +67,12 @@ typedef struct {
   void *stream;         /* hipStream_t; NULL = the stream set by distr_attn_set_stream (default: null stream) */
   void *workspace;      /* device scratch of >= distr_attn_workspace_bytes(), 256-byte aligned; NULL =
                            library-owned, one per device, grown on demand (hipMalloc on first use /
-                           growth, after a device synchronise). Calls that may overlap in time on
-                           different streams must each bring their own workspace.                   */
+                           growth; outgrown buffers are kept until distr_attn_release; growing
+                           while the stream is being captured into a graph is refused). Calls that
+                           may overlap in time on different streams must each bring their own
+                           workspace. Only what the call writes is needed: no K^T part with kt_in,
+                           no table with perm_in / perm_out or when the attention kernel does the
+                           LSH stage itself.                                                        */
   size_t workspace_bytes;
   uint8_t *perm_out;    /* optional device [B][H][Tq][d]: channel at sorted position s of each block */
   uint32_t *hash_out;   /* optional device [B][H][Tq][d]: hash of each channel of each block          */
@@ -70,6 +80,15 @@ typedef struct {
                              (each row must be a permutation of 0..d-1; it is not checked)          */
   const void *kt_in;      /* optional device buffer written by distr_attn_key_prepass for this k and
                              n_groups: skip the key pre-pass (bf16 only)                            */
+  int Nk;               /* keys / values per head; 0 means N. N != Nk covers decoding against a cache
+                           and cross attention (Sec. 2.1 with an N x Nk score matrix). With causal = 1
+                           (needs Nk >= N) the last query is aligned with the last key: key n is
+                           visible to query i iff n <= i + (Nk - N)                                */
+  int side;             /* 0: sample Q columns, fuse K columns, one grouping per Q block (Sec. 3.2-3.3,
+                           the form the paper builds). 1: the mirrored form of Sec. 3.1 / Fig. 4 right:
+                           sample K columns, fuse Q columns, one grouping per K block of Bc rows taken
+                           from that K block; float only, Bc in {32, 64, 128}; perm_in / perm_out /
+                           hash_out are then [B][Hkv][Tk][d]                                        */
 } da_params;
 
 /*
@@ -96,13 +115,14 @@ int distr_attn_exact_fwd_ex(const void *q, const void *k, const void *v, void *o
  * LSH hash-and-group stage alone (Sec. 3.2 "similar columns identification", Fig. 5): writes
  * p->perm_out and/or p->hash_out (at least one must be given). Projections are accumulated in
  * float with one fused multiply-add per row, rows ascending; bit of plane 0 is the most
- * significant; channels are sorted by (hash, channel index) ascending.
+ * significant; channels are sorted by (hash, channel index) ascending. With p->side = 1 the
+ * tensor is K ([B][Hkv][Nk][d]) and the blocks are its K blocks of Bc rows.
  */
 int distr_attn_lsh_group(const void *q, const da_params *p);
 
 /*
- * Key pre-pass of the bf16 DistrAttention path alone: k [B][Hkv][N][d] bf16 -> kt_out
- * [B][Hkv][d][Npad] half, keys fastest, Npad = N rounded up to 64, tail zero-filled, values
+ * Key pre-pass of the bf16 DistrAttention path alone: k [B][Hkv][Nk][d] bf16 -> kt_out
+ * [B][Hkv][d][Npad] half, keys fastest, Npad = Nk rounded up to 64, tail zero-filled, values
  * clamped to +-65504/G* so that a group's sum (Sec. 3.2 fusion) stays finite in half. The fusion
  * then adds whole channel rows. distr_attn_fwd_ex runs it into its workspace unless kt_in is given.
  * kt_out: device, distr_attn_kt_bytes(p) bytes, 256-byte aligned.

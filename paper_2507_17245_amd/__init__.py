@@ -33,6 +33,7 @@ class DaParams(ctypes.Structure):
         ("stream", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_size_t), ("perm_out", ctypes.c_void_p),
         ("hash_out", ctypes.c_void_p), ("perm_in", ctypes.c_void_p), ("kt_in", ctypes.c_void_p),
+        ("Nk", ctypes.c_int), ("side", ctypes.c_int),
     ]
 
 
@@ -95,10 +96,10 @@ def _dtype_code(t):
 
 
 def _shapes(q, k, v):
-    if q.dim() != 4 or k.dim() != 4 or v.shape != k.shape:
-        raise ValueError("q must be [B,H,N,d]; k, v must be [B,Hkv,N,d]")
+    if q.dim() != 4 or k.dim() != 4 or tuple(v.shape) != tuple(k.shape):
+        raise ValueError("q must be [B,H,N,d]; k, v must be [B,Hkv,Nk,d]")
     B, H, N, d = q.shape
-    if k.shape[0] != B or k.shape[2] != N or k.shape[3] != d:
+    if k.shape[0] != B or k.shape[3] != d:
         raise ValueError("k, v do not match q")
     for t in (q, k, v):
         if not t.is_cuda or not t.is_contiguous():
@@ -130,10 +131,15 @@ def _check_buffer(t, name, min_bytes):
 
 def make_params(q, k, v, Br, Bc=64, n_groups=None, causal=False, lsh_seed=0, n_planes=0,
                 softmax_scale=0.0, gray_mode=0, workspace=None, perm_out=None, hash_out=None,
-                perm_in=None, kt_in=None):
+                perm_in=None, kt_in=None, side=0):
+    """side=1: the mirrored form (sample K, fuse Q, one grouping per K block of Bc rows); the
+    tables are then [B, Hkv, ceil(Nk/Bc), d]. Nk is taken from k's shape."""
     B, H, Hkv, N, d = _shapes(q, k, v)
+    Nk = k.shape[2]
     p = DaParams()
     p.B, p.H, p.Hkv, p.N, p.d, p.Br, p.Bc = B, H, Hkv, N, d, Br, Bc
+    p.Nk = Nk
+    p.side = side
     p.n_groups = d if n_groups is None else n_groups
     p.causal = int(bool(causal))
     p.lsh_seed = lsh_seed
@@ -142,7 +148,10 @@ def make_params(q, k, v, Br, Bc=64, n_groups=None, causal=False, lsh_seed=0, n_p
     p.softmax_scale = softmax_scale
     p.gray_mode = gray_mode
     p.stream = _current_stream().value
-    n_table = B * H * ((N + Br - 1) // Br) * d if Br > 0 else 0
+    if side == 1:
+        n_table = B * Hkv * ((Nk + Bc - 1) // Bc) * d if Bc > 0 else 0
+    else:
+        n_table = B * H * ((N + Br - 1) // Br) * d if Br > 0 else 0
     _check_buffer(workspace, "workspace", 0)
     _check_buffer(perm_out, "perm_out", n_table)
     _check_buffer(hash_out, "hash_out", 4 * n_table)
@@ -166,6 +175,8 @@ def distr_attn_fwd(q, k, v, o, Br, Bc, n_groups, lsh_seed=0, causal=False):
         raise TypeError("the short form takes bf16 tensors; use distr_attn_fwd_ex for float")
     _check_out(q, o)
     lib().distr_attn_set_stream(_current_stream())
+    if k.shape[2] != N:
+        raise ValueError("the short form takes N keys; use distr_attn_fwd_ex for Nk != N")
     _check(lib().distr_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), B, H, Hkv, N, d, Br, Bc,
                                 n_groups, lsh_seed, int(bool(causal))))
     return o
@@ -177,6 +188,8 @@ def distr_attn_exact_fwd(q, k, v, o, Br, Bc, causal=False):
         raise TypeError("the short form takes bf16 tensors; use distr_attn_exact_fwd_ex for float")
     _check_out(q, o)
     lib().distr_attn_set_stream(_current_stream())
+    if k.shape[2] != N:
+        raise ValueError("the short form takes N keys; use distr_attn_exact_fwd_ex for Nk != N")
     _check(lib().distr_attn_exact_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), B, H, Hkv, N, d, Br, Bc,
                                       int(bool(causal))))
     return o
@@ -185,7 +198,8 @@ def distr_attn_exact_fwd(q, k, v, o, Br, Bc, causal=False):
 def _check_ex(q, k, v, o, params):
     B, H, Hkv, N, d = _shapes(q, k, v)
     _check_out(q, o)
-    if (params.B, params.H, params.Hkv, params.N, params.d, params.dtype) != (B, H, Hkv, N, d, _dtype_code(q)):
+    if (params.B, params.H, params.Hkv, params.N, params.d, params.dtype, params.Nk or N) != \
+            (B, H, Hkv, N, d, _dtype_code(q), k.shape[2]):
         raise ValueError("params were made for tensors of another shape or dtype")
 
 

@@ -43,7 +43,8 @@ int fail(int code, const char* fmt, ...) {
 struct Resolved {
   da::Problem pb;
   int dtype;
-  int Tq;
+  int Tq;        // query blocks per head
+  int Tk_side;   // K blocks per head whose groupings the mirrored form (side 1) uses
   hipStream_t stream;
 };
 
@@ -55,6 +56,11 @@ int resolve(const da_params* p, bool need_groups, Resolved* out) {
   if (p->H % p->Hkv != 0) return fail(DA_ERR_INVALID_ARG, "H (%d) is not a multiple of Hkv (%d)", p->H, p->Hkv);
   if (p->dtype != DA_BF16 && p->dtype != DA_F32) return fail(DA_ERR_INVALID_ARG, "unknown dtype %d", p->dtype);
   if (p->causal != 0 && p->causal != 1) return fail(DA_ERR_INVALID_ARG, "causal must be 0 or 1");
+  if (p->Nk < 0) return fail(DA_ERR_INVALID_ARG, "Nk must be positive, or 0 for Nk = N");
+  const int Nk = p->Nk > 0 ? p->Nk : p->N;
+  if (p->causal && Nk < p->N)
+    return fail(DA_ERR_INVALID_ARG, "causal with Nk (%d) < N (%d): the first queries would see no key", Nk, p->N);
+  if (p->side != 0 && p->side != 1) return fail(DA_ERR_INVALID_ARG, "side must be 0 or 1");
   int n_planes = p->n_planes == 0 ? 16 : p->n_planes;
   if (need_groups) {
     if (p->n_groups <= 0 || p->d % p->n_groups != 0)
@@ -68,16 +74,25 @@ int resolve(const da_params* p, bool need_groups, Resolved* out) {
   if ((long long)p->B * p->H * ((p->N + p->Br - 1) / p->Br) > 0x7fffffffLL)
     return fail(DA_ERR_UNSUPPORTED, "more than 2^31-1 query blocks");
   // limits of the kernels
-  if ((long long)p->N * p->d * 4 > 0x7fffffffLL)
-    return fail(DA_ERR_UNSUPPORTED, "N * d = %lld: one head must stay below 2 GiB (32-bit tile offsets)", (long long)p->N * p->d);
+  const long long n_max = p->N > Nk ? p->N : Nk;
+  if (n_max * p->d * 4 > 0x7fffffffLL)
+    return fail(DA_ERR_UNSUPPORTED, "N * d = %lld: one head must stay below 2 GiB (32-bit tile offsets)", n_max * p->d);
   if (p->d != 64 && p->d != 128) return fail(DA_ERR_UNSUPPORTED, "d = %d: kernels are built for d in {64, 128}", p->d);
   if (p->Br != 64 && p->Br != 128) return fail(DA_ERR_UNSUPPORTED, "Br = %d: kernels are built for Br in {64, 128}", p->Br);
-  if (p->Bc != 64) return fail(DA_ERR_UNSUPPORTED, "Bc = %d: kernels are built for Bc = 64", p->Bc);
+  const bool mirrored = need_groups && p->side == 1;
+  if (mirrored) {
+    if (p->dtype != DA_F32) return fail(DA_ERR_UNSUPPORTED, "side = 1 (sample K, fuse Q) is built for the float path only");
+    if (p->Bc != 32 && p->Bc != 64 && p->Bc != 128)
+      return fail(DA_ERR_UNSUPPORTED, "Bc = %d: side = 1 groups K blocks of 32, 64 or 128 rows", p->Bc);
+  } else if (p->Bc != 64) {
+    return fail(DA_ERR_UNSUPPORTED, "Bc = %d: kernels are built for Bc = 64", p->Bc);
+  }
   if (need_groups && n_planes > da::kMaxPlanes) return fail(DA_ERR_UNSUPPORTED, "n_planes = %d > %d", n_planes, da::kMaxPlanes);
   out->pb = da::Problem{p->B, p->H, p->Hkv, p->N, p->d, p->Br, need_groups ? p->n_groups : p->d,
-                        p->causal, n_planes, p->gray_mode, p->lsh_seed, scale};
+                        p->causal, n_planes, p->gray_mode, p->lsh_seed, scale, Nk, mirrored ? 1 : 0, p->Bc};
   out->dtype = p->dtype;
   out->Tq = (p->N + p->Br - 1) / p->Br;
+  out->Tk_side = (Nk + p->Bc - 1) / p->Bc;
   out->stream = (hipStream_t)(p->stream ? p->stream : g_stream.load());
   return DA_OK;
 }
@@ -92,15 +107,26 @@ int check_tensors(const void* q, const void* k, const void* v, const void* o) {
   return DA_OK;
 }
 
+// Table of groupings: one row of d channels per Q block, or per K block for the mirrored form.
 size_t perm_bytes(const Resolved& r) {
-  size_t n = (size_t)r.pb.B * r.pb.H * r.Tq * r.pb.d;
+  size_t n = r.pb.side == 1 ? (size_t)r.pb.B * r.pb.Hkv * r.Tk_side * r.pb.d
+                            : (size_t)r.pb.B * r.pb.H * r.Tq * r.pb.d;
   return (n + 255) & ~(size_t)255;
+}
+
+// The LSH stage as the mirrored form needs it: over K, one block of Bc rows at a time.
+da::Problem key_side_problem(const da::Problem& pb) {
+  da::Problem k = pb;
+  k.H = pb.Hkv;
+  k.N = pb.Nk;
+  k.Br = pb.Bc;
+  return k;
 }
 
 // Transposed half-precision copy of K that the bf16 distr path reads: [B][Hkv][d][Npad].
 size_t kt_bytes(const Resolved& r) {
   if (r.dtype != DA_BF16) return 0;
-  size_t npad = (size_t)((r.pb.N + da::kBc - 1) / da::kBc) * da::kBc;
+  size_t npad = (size_t)((r.pb.Nk + da::kBc - 1) / da::kBc) * da::kBc;
   size_t n = (size_t)r.pb.B * r.pb.Hkv * r.pb.d * npad * 2;
   return (n + 255) & ~(size_t)255;
 }
@@ -211,7 +237,10 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
       perm = p->perm_in;
     } else if (run_lsh) {
       if (p->perm_out) table = p->perm_out;
-      rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, table, p->hash_out, r.stream), "lsh_group launch");
+      rc = check_launch(r.pb.side == 1
+                            ? da::launch_lsh_group(k, r.dtype, key_side_problem(r.pb), table, p->hash_out, r.stream)
+                            : da::launch_lsh_group(q, r.dtype, r.pb, table, p->hash_out, r.stream),
+                        "lsh_group launch");
       if (rc) return rc;
       perm = table;
     }
@@ -273,7 +302,9 @@ int distr_attn_lsh_group(const void* q, const da_params* p) {
   if (rc) return rc;
   if (!q) return fail(DA_ERR_INVALID_ARG, "q must be non-null");
   if (!p->perm_out && !p->hash_out) return fail(DA_ERR_INVALID_ARG, "perm_out or hash_out must be given");
-  return check_launch(da::launch_lsh_group(q, r.dtype, r.pb, p->perm_out, p->hash_out, r.stream), "lsh_group launch");
+  // side 1: the tensor is K ([B][Hkv][Nk][d]) and the blocks are its Bc-row K blocks
+  return check_launch(da::launch_lsh_group(q, r.dtype, r.pb.side == 1 ? key_side_problem(r.pb) : r.pb, p->perm_out,
+                                           p->hash_out, r.stream), "lsh_group launch");
 }
 
 int distr_attn_key_prepass(const void* k, void* kt_out, const da_params* p) {

@@ -147,7 +147,7 @@ template <int D, int BR, int KRED, bool DISTR, int NG>
 __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     bf16* __restrict__ o, const uint8_t* __restrict__ perm, const f16* __restrict__ kt, int Npad,
-    int H, int Hkv, int N, int Tq, int causal, float scale_log2e, int total_units, int n_planes,
+    int H, int Hkv, int N, int Nk, int Tq, int causal, float scale_log2e, int total_units, int n_planes,
     int gray_mode, uint64_t lsh_seed) {
   using C = Cfg<D, BR, KRED, DISTR, NG>;
   using kx8 = typename std::conditional<DISTR, f16x8, bf16x8>::type;
@@ -196,8 +196,11 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
   const int r0 = t * BR;
 
   const bf16* qh = q + (size_t)bh * N * D;
-  const bf16* kh = k + (size_t)(b * Hkv + hk) * N * D;
-  const bf16* vh = v + (size_t)(b * Hkv + hk) * N * D;
+  const bf16* kh = k + (size_t)(b * Hkv + hk) * Nk * D;
+  const bf16* vh = v + (size_t)(b * Hkv + hk) * Nk * D;
+  // N queries against Nk keys; under the causal mask the last query is aligned with the last
+  // key: key n is visible to query i iff n <= i + shift.
+  const int shift = Nk - N;
 
   const int qw0 = r0 + wave * 32;              // first query row of this wave
   const int q_abs = qw0 + lq;                  // this lane's query row
@@ -326,16 +329,16 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
     }
   }
 
-  const int n_end = causal ? min(N, r0 + BR) : N;
+  const int n_end = causal ? min(Nk, r0 + BR + shift) : Nk;
   const int n_tiles = (n_end + kBc - 1) / kBc;
   // tiles [0, n_full) need no masking for any row of the block
-  const int n_full = causal ? min(r0, N) / kBc : N / kBc;
+  const int n_full = causal ? min(r0 + shift, Nk) / kBc : Nk / kBc;
 
   // ---- tile loads: global -> LDS ---------------------------------------------------------------
   // K and V rows are fetched through buffer descriptors: the per-lane byte offset inside a
   // tile is fixed, the tile advances through the scalar offset, and rows past the end of the
   // head read as zero (hardware range check), so a tile costs no address arithmetic.
-  const unsigned head_bytes = (unsigned)N * D * 2;
+  const unsigned head_bytes = (unsigned)Nk * D * 2;
   const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kh, 0, head_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)vh, 0, head_bytes, 0x00020000);
 
@@ -471,7 +474,7 @@ __global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
 
   // Causal / ragged-tail mask of the scores of tile `tile`.
   auto apply_mask = [&](int tile, f32x16 (&sc)[2]) {
-    const int lim = causal ? min(q_abs, N - 1) : N - 1;  // last visible key of this row
+    const int lim = causal ? min(q_abs + shift, Nk - 1) : Nk - 1;  // last visible key of this row
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -663,7 +666,7 @@ hipError_t launch_one(const void* q, const void* k, const void* v, void* o, cons
   const int causal_mode = pb.causal ? (units <= 8 * 256 ? 2 : 1) : 0;
   hipLaunchKernelGGL((attn_bf16_kernel<D, BR, KRED, DISTR, NG>), dim3((unsigned)units), dim3(BR * 2), 0,
                      stream, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, perm, (const f16*)kt,
-                     (pb.N + kBc - 1) / kBc * kBc, pb.H, pb.Hkv, pb.N, Tq, causal_mode, scale_log2e, (int)units,
+                     (pb.Nk + kBc - 1) / kBc * kBc, pb.H, pb.Hkv, pb.N, pb.Nk, Tq, causal_mode, scale_log2e, (int)units,
                      pb.n_planes, pb.gray_mode, pb.seed);
   return hipGetLastError();
 }

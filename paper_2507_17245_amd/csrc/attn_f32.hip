@@ -7,6 +7,12 @@
 // K/V tiles of 32 rows go through LDS; the fused tile K_f is built in LDS once per (Q block,
 // K tile) and shared by the block's rows; the softmax is online per tile (Sec. 2.2.2).
 // Built for accuracy checks on small problems.
+//
+// side = 1 is the mirrored form of Sec. 3.1 (last sentence of the Eq. 2 paragraph, Fig. 4 right
+// side): the grouping belongs to the K block (Bc rows, table [B][Hkv][Tk][d] from the LSH
+// stage run on K), one K column per group is sampled and the group's Q columns are summed.
+// Every K block then needs its own permutation and its own fused queries -- the reloading
+// Sec. 3.3 gives as the reason for sampling Q instead.
 #include "da_common.h"
 
 namespace da {
@@ -17,8 +23,8 @@ constexpr int kF32Lanes = 4;  // lanes per query row
 template <int D, int BR>
 __global__ __launch_bounds__(BR * kF32Lanes) void attn_f32_kernel(
     const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ v,
-    float* __restrict__ o, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Tq,
-    int n_groups, int causal, float scale, int distr) {
+    float* __restrict__ o, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Nk, int Tq,
+    int n_groups, int causal, float scale, int distr, int side, int Bc) {
   constexpr int T = BR * kF32Lanes;
   constexpr int QS = D / kF32Lanes;            // most channels of the score product one lane takes
   constexpr int CS = D / kF32Lanes;            // output channels per lane
@@ -40,10 +46,13 @@ __global__ __launch_bounds__(BR * kF32Lanes) void attn_f32_kernel(
   const int G = D / kred;
 
   const float* qh = q + ((size_t)bh * N + r0) * D;
-  const float* kh = k + ((size_t)(b * Hkv + hk) * N) * D;
-  const float* vh = v + ((size_t)(b * Hkv + hk) * N) * D;
+  const float* kh = k + ((size_t)(b * Hkv + hk) * Nk) * D;
+  const float* vh = v + ((size_t)(b * Hkv + hk) * Nk) * D;
+  const int shift = Nk - N;   // causal: key n is visible to query i iff n <= i + shift
+  const bool mirrored = distr && side == 1;
+  const int Tk = (Nk + Bc - 1) / Bc;
 
-  if (distr)
+  if (distr && !mirrored)
     // D is a power of two: an out-of-range entry of a caller's table cannot index past a row
     for (int i = tid; i < D; i += T) perm_lds[i] = perm[(size_t)blockIdx.x * D + i] & (D - 1);
   __syncthreads();
@@ -55,25 +64,45 @@ __global__ __launch_bounds__(BR * kF32Lanes) void attn_f32_kernel(
 #pragma unroll
   for (int i = 0; i < QS; ++i) {
     const int j = part + kF32Lanes * i;
-    qreg[i] = (active && j < kred) ? qh[(size_t)row * D + (distr ? perm_lds[j * G] : j)] : 0.0f;
+    qreg[i] = (active && j < kred && !mirrored) ? qh[(size_t)row * D + (distr ? perm_lds[j * G] : j)] : 0.0f;
   }
 
   float acc[CS];
 #pragma unroll
   for (int c = 0; c < CS; ++c) acc[c] = 0.0f;
   float m_run = -INFINITY, l_run = 0.0f;
-  const int n_end = causal ? min(N, r0 + rows) : N;
+  const int n_end = causal ? min(Nk, r0 + rows + shift) : Nk;
 
   for (int n0 = 0; n0 < n_end; n0 += kF32Tile) {
     const int tn = min(kF32Tile, n_end - n0);
     __syncthreads();
+    if (mirrored && n0 % Bc == 0) {
+      // a new K block: its permutation, and the queries fused by it (members in sorted order)
+      const size_t pbase = (((size_t)(b * Hkv + hk)) * Tk + n0 / Bc) * D;
+      for (int i = tid; i < D; i += T) perm_lds[i] = perm[pbase + i] & (D - 1);
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < QS; ++i) {
+        const int j = part + kF32Lanes * i;
+        float s = 0.0f;
+        if (active && j < kred)
+          for (int g = 0; g < G; ++g) s += qh[(size_t)row * D + perm_lds[j * G + g]];
+        qreg[i] = s;
+      }
+    }
     for (int i = tid; i < tn * D; i += T) {
       int n = i / D, c = i % D;
       k_lds[n][c] = kh[(size_t)(n0 + n) * D + c];
       v_lds[n][c] = vh[(size_t)(n0 + n) * D + c];
     }
     __syncthreads();
-    if (distr) {  // fusion: sum the group's key channels, members in sorted order
+    if (mirrored) {  // sampling on the K side: the group's first channel in sorted order
+      for (int i = tid; i < tn * kred; i += T) {
+        int n = i / kred, j = i % kred;
+        kf_lds[n][j] = k_lds[n][perm_lds[j * G]];
+      }
+      __syncthreads();
+    } else if (distr) {  // fusion: sum the group's key channels, members in sorted order
       for (int i = tid; i < tn * kred; i += T) {
         int n = i / kred, j = i % kred;
         float s = 0.0f;
@@ -99,7 +128,7 @@ __global__ __launch_bounds__(BR * kF32Lanes) void attn_f32_kernel(
       s += __shfl_xor(s, 1);
       s += __shfl_xor(s, 2);
       s *= scale;
-      if (n >= tn || (causal && n0 + n > i_abs)) s = -INFINITY;
+      if (n >= tn || (causal && n0 + n > i_abs + shift)) s = -INFINITY;
       sc[n] = s;
       m_tile = fmaxf(m_tile, s);
     }
@@ -141,8 +170,8 @@ hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o,
   dim3 grid((unsigned)units);
 #define DA_F32_LAUNCH(DD, BB)                                                                      \
   hipLaunchKernelGGL((attn_f32_kernel<DD, BB>), grid, dim3(BB * kF32Lanes), 0, stream, (const float*)q,        \
-                     (const float*)k, (const float*)v, (float*)o, perm, pb.H, pb.Hkv, pb.N, Tq,    \
-                     pb.n_groups, pb.causal, pb.scale, distr)
+                     (const float*)k, (const float*)v, (float*)o, perm, pb.H, pb.Hkv, pb.N, pb.Nk, Tq, \
+                     pb.n_groups, pb.causal, pb.scale, distr, pb.side, pb.Bc)
   if (pb.d == 64 && pb.Br == 64) DA_F32_LAUNCH(64, 64);
   else if (pb.d == 64 && pb.Br == 128) DA_F32_LAUNCH(64, 128);
   else if (pb.d == 128 && pb.Br == 64) DA_F32_LAUNCH(128, 64);

@@ -45,12 +45,17 @@ struct Problem {
   int B, H, Hkv, N, d, Br, n_groups, causal, n_planes, gray_mode;
   uint64_t seed;
   float scale;
+  int Nk;     // keys / values per head (N is the number of queries); causal: key n is visible
+              // to query i iff n <= i + (Nk - N)
+  int side;   // 0: sample Q, fuse K, one grouping per Q block; 1: sample K, fuse Q, one grouping
+              // per K block of Bc rows (float path only)
+  int Bc;     // rows of a K block (only side 1 depends on it)
 };
 
 // Launchers (defined next to their kernels). All return hipError_t of the launch.
 hipError_t launch_lsh_group(const void* q, int dtype, const Problem& pb, uint8_t* perm_out,
                             uint32_t* hash_out, hipStream_t stream);
-// K [B][Hkv][N][d] bf16 -> K^T [B][Hkv][d][Npad] half (Npad = N rounded up to kBc), for the distr path.
+// K [B][Hkv][Nk][d] bf16 -> K^T [B][Hkv][d][Npad] half (Npad = Nk rounded up to kBc), for the distr path.
 hipError_t launch_kt_prepass(const void* k, void* kt, const Problem& pb, hipStream_t stream);
 // distr != 0: S^ = Q_r K_f^T with the per-block permutation table `perm` [B][H][Tq][d] and the
 // transposed keys `kt` written by launch_kt_prepass (k itself is then unused).

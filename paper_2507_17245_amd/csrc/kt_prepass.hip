@@ -1,4 +1,4 @@
-// Key pre-pass of the DistrAttention path: K [B][Hkv][N][d] (bf16, d fastest) is rewritten once
+// Key pre-pass of the DistrAttention path: K [B][Hkv][Nk][d] (bf16, d fastest) is rewritten once
 // per forward as K^T [B][Hkv][d][Npad] in half precision (keys fastest, Npad = N rounded up to
 // the 64-key tile, tail zero-filled).
 //
@@ -57,15 +57,15 @@ __global__ __launch_bounds__(kKtThreads) void kt_prepass_kernel(const bf16* __re
 }
 
 hipError_t launch_kt_prepass(const void* k, void* kt, const Problem& pb, hipStream_t stream) {
-  const int Tk = (pb.N + kBc - 1) / kBc;
+  const int Tk = (pb.Nk + kBc - 1) / kBc;
   const int Npad = Tk * kBc;
   const long long units = (long long)pb.B * pb.Hkv * Tk;
   const float limit = 65504.0f / (float)(pb.d / pb.n_groups);
   dim3 grid((unsigned)units), block(kKtThreads);
   if (pb.d == 64)
-    hipLaunchKernelGGL((kt_prepass_kernel<64>), grid, block, 0, stream, (const bf16*)k, (f16*)kt, pb.N, Npad, Tk, limit);
+    hipLaunchKernelGGL((kt_prepass_kernel<64>), grid, block, 0, stream, (const bf16*)k, (f16*)kt, pb.Nk, Npad, Tk, limit);
   else if (pb.d == 128)
-    hipLaunchKernelGGL((kt_prepass_kernel<128>), grid, block, 0, stream, (const bf16*)k, (f16*)kt, pb.N, Npad, Tk, limit);
+    hipLaunchKernelGGL((kt_prepass_kernel<128>), grid, block, 0, stream, (const bf16*)k, (f16*)kt, pb.Nk, Npad, Tk, limit);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

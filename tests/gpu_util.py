@@ -23,14 +23,15 @@ def run_gpu(cfg, q, k, v, distr=True, want_tables=False, n_groups=None, lsh_seed
     o = torch.full_like(tq, float("nan"))
     perm = hsh = None
     if want_tables:
-        perm = torch.zeros((cfg.B, cfg.H, cfg.Tq, cfg.d), dtype=torch.uint8, device="cuda")
-        hsh = torch.zeros((cfg.B, cfg.H, cfg.Tq, cfg.d), dtype=torch.int32, device="cuda")
+        shape = (cfg.B, cfg.Hkv, cfg.Tk, cfg.d) if cfg.side == 1 else (cfg.B, cfg.H, cfg.Tq, cfg.d)
+        perm = torch.zeros(shape, dtype=torch.uint8, device="cuda")
+        hsh = torch.zeros(shape, dtype=torch.int32, device="cuda")
     t_perm_in = None if perm_in is None else torch.from_numpy(np.ascontiguousarray(perm_in, dtype=np.uint8)).cuda()
     p = da.make_params(tq, tk, tv, Br=cfg.Br, Bc=cfg.Bc,
                        n_groups=cfg.n_groups if n_groups is None else n_groups, causal=cfg.causal,
                        lsh_seed=cfg.lsh_seed if lsh_seed is None else lsh_seed,
                        n_planes=cfg.n_planes, gray_mode=gray_mode, perm_out=perm, hash_out=hsh,
-                       softmax_scale=scale, perm_in=t_perm_in)
+                       softmax_scale=scale, perm_in=t_perm_in, side=cfg.side)
     if distr:
         da.distr_attn_fwd_ex(tq, tk, tv, o, p)
     else:
@@ -58,7 +59,18 @@ def oracle_params(cfg, n_groups=None, lsh_seed=None, gray_mode=0, scale=None):
     return oracle.params(cfg.B, cfg.H, cfg.Hkv, cfg.N, cfg.d, cfg.Br,
                          cfg.n_groups if n_groups is None else n_groups, causal=cfg.causal,
                          n_planes=cfg.n_planes, gray_mode=gray_mode,
-                         lsh_seed=cfg.lsh_seed if lsh_seed is None else lsh_seed, scale=scale)
+                         lsh_seed=cfg.lsh_seed if lsh_seed is None else lsh_seed, scale=scale,
+                         Nk=cfg.n_keys, side=cfg.side, Bc=cfg.Bc)
+
+
+def oracle_tables(cfg, q, k, gray_mode=0):
+    """(hash, perm) of the blocks the grouping is taken from: the Q blocks, or, for the mirrored
+    form, the K blocks of Bc rows of every kv head."""
+    if cfg.side == 1:
+        pk = oracle.params(cfg.B, cfg.Hkv, cfg.Hkv, cfg.n_keys, cfg.d, cfg.Bc, cfg.n_groups, n_planes=cfg.n_planes,
+                           gray_mode=gray_mode, lsh_seed=cfg.lsh_seed)
+        return oracle.lsh_group(k, pk)[:2]
+    return oracle.lsh_group(q, oracle_params(cfg, gray_mode=gray_mode))[:2]
 
 
 def assert_close(got, want, dtype, what="", recorded=None):

@@ -32,6 +32,16 @@ class Config:
     recipe: str       # value structure, see make()
     data_seed: int
     lsh_seed: int = 0
+    Nk: int = 0       # keys / values per head; 0 = N (decode against a cache, cross attention: Nk != N)
+    side: int = 0     # 1 = the mirrored form (sample K, fuse Q, one grouping per K block of Bc rows)
+
+    @property
+    def n_keys(self):
+        return self.Nk if self.Nk > 0 else self.N
+
+    @property
+    def Tk(self):
+        return (self.n_keys + self.Bc - 1) // self.Bc
 
     @property
     def Tq(self):
@@ -72,7 +82,7 @@ def make(cfg: Config):
     """-> (q, k, v) float32 arrays for the configuration, deterministic in cfg.data_seed."""
     rng = np.random.default_rng(cfg.data_seed)
     B, H, Hkv, N, d = cfg.B, cfg.H, cfg.Hkv, cfg.N, cfg.d
-    qs, ks = (B, H, N, d), (B, Hkv, N, d)
+    qs, ks = (B, H, N, d), (B, Hkv, cfg.n_keys, d)
     pi = rng.permutation(d)  # partner channels are not index neighbours
     if cfg.recipe == "latent_pairs":
         # d/2 latent columns per head; channels pi[2p], pi[2p+1] = latent p + 0.1 noise each
@@ -115,7 +125,7 @@ def make(cfg: Config):
             x = np.empty(shape, dtype=np.float32)
             for b in range(shape[0]):
                 for h in range(shape[1]):
-                    x[b, h] = _normal(rng, (N, rank)) @ w[h] + 0.3 * _normal(rng, (N, d))
+                    x[b, h] = _normal(rng, (shape[2], rank)) @ w[h] + 0.3 * _normal(rng, (shape[2], d))
             return x
         w = _normal(rng, (H, rank, d)) / np.float32(np.sqrt(rank))
         q = lowrank(qs, w)
