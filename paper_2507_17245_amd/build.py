@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libdistr_attn.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "lsh_group.hip", "kt_prepass.hip", "attn_bf16.hip", "attn_f32.hip"]
+SOURCES = ["attn_bf16_bc64.hip", "attn_bf16_bc128.hip", "attn_bf16_bc32.hip", "api.hip", "lsh_group.hip",
+           "kt_prepass.hip", "attn_bf16.hip", "attn_f32.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          # packed-fp32 VALU forms are switched off for every kernel of this library

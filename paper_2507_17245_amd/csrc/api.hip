@@ -78,14 +78,15 @@ int resolve(const da_params* p, bool need_groups, Resolved* out) {
   if (n_max * p->d * 4 > 0x7fffffffLL)
     return fail(DA_ERR_UNSUPPORTED, "N * d = %lld: one head must stay below 2 GiB (32-bit tile offsets)", n_max * p->d);
   if (p->d != 64 && p->d != 128) return fail(DA_ERR_UNSUPPORTED, "d = %d: kernels are built for d in {64, 128}", p->d);
-  if (p->Br != 64 && p->Br != 128) return fail(DA_ERR_UNSUPPORTED, "Br = %d: kernels are built for Br in {64, 128}", p->Br);
+  if (p->Br != 64 && p->Br != 128 && p->Br != 256)
+    return fail(DA_ERR_UNSUPPORTED, "Br = %d: kernels are built for Br in {64, 128, 256}", p->Br);
   const bool mirrored = need_groups && p->side == 1;
   if (mirrored) {
     if (p->dtype != DA_F32) return fail(DA_ERR_UNSUPPORTED, "side = 1 (sample K, fuse Q) is built for the float path only");
     if (p->Bc != 32 && p->Bc != 64 && p->Bc != 128)
       return fail(DA_ERR_UNSUPPORTED, "Bc = %d: side = 1 groups K blocks of 32, 64 or 128 rows", p->Bc);
-  } else if (p->Bc != 64) {
-    return fail(DA_ERR_UNSUPPORTED, "Bc = %d: kernels are built for Bc = 64", p->Bc);
+  } else if (p->Bc != 32 && p->Bc != 64 && p->Bc != 128) {
+    return fail(DA_ERR_UNSUPPORTED, "Bc = %d: kernels are built for Bc in {32, 64, 128}", p->Bc);
   }
   if (need_groups && n_planes > da::kMaxPlanes) return fail(DA_ERR_UNSUPPORTED, "n_planes = %d > %d", n_planes, da::kMaxPlanes);
   out->pb = da::Problem{p->B, p->H, p->Hkv, p->N, p->d, p->Br, need_groups ? p->n_groups : p->d,
@@ -126,7 +127,7 @@ da::Problem key_side_problem(const da::Problem& pb) {
 // Transposed half-precision copy of K that the bf16 distr path reads: [B][Hkv][d][Npad].
 size_t kt_bytes(const Resolved& r) {
   if (r.dtype != DA_BF16) return 0;
-  size_t npad = (size_t)((r.pb.Nk + da::kBc - 1) / da::kBc) * da::kBc;
+  size_t npad = (size_t)((r.pb.Nk + da::kKtPad - 1) / da::kKtPad) * da::kKtPad;
   size_t n = (size_t)r.pb.B * r.pb.Hkv * r.pb.d * npad * 2;
   return (n + 255) & ~(size_t)255;
 }
@@ -210,8 +211,8 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
   rc = check_tensors(q, k, v, o);
   if (rc) return rc;
   if (r.dtype == DA_BF16 && !da::attn_bf16_supported(r.pb, distr ? 1 : 0))
-    return fail(DA_ERR_UNSUPPORTED, "bf16 kernels need n_groups in {4, 8, 16, 32, 64, 128} and groups of at most 16 channels; "
-                "got d=%d Br=%d n_groups=%d", p->d, p->Br, p->n_groups);
+    return fail(DA_ERR_UNSUPPORTED, "bf16 kernels need n_groups in {4, 8, 16, 32, 64, 128} (16, 32, 64 or d when Bc is not "
+                "64) and groups of at most 16 channels; got d=%d Br=%d Bc=%d n_groups=%d", p->d, p->Br, p->Bc, p->n_groups);
   const uint8_t* perm = nullptr;
   void* kt = nullptr;
   // Groups of one channel (G* = 1): S^ = Q_r K_f^T is Q K^T with its terms taken in the sorted

@@ -1,703 +1,28 @@
-// Tiled bf16 attention forward for gfx950 (CDNA4): exact attention (Sec. 2.1, tiled as in
-// Sec. 2.2.2) and DistrAttention (Sec. 3.1 Eq. 2, Sec. 3.2 sampling and fusion, Sec. 3.3
-// block-wise grouping) from one template.
-//
-// Work split. One workgroup owns one Q block of BR rows of one (batch, head); each of its
-// BR/32 wavefronts owns 32 query rows for the whole inner loop over K/V tiles of 64 rows.
-//
-// Matrix-core mapping (v_mfma_f32_32x32x16_bf16, fp32 accumulate). Both products are taken
-// transposed so that one lane owns one query row's softmax state:
-//   S^T[kv][q] = sum_c  Kx[kv][c] * Qx[q][c]      A = Kx tile rows from LDS, B = Qx in registers
-//   O^T[ch][q] = sum_kv V[kv][ch] * P^T[kv][q]    A = V^T via LDS transpose reads, B = P^T in registers
-// The accumulator layout of the first product (lane = q, registers = kv) is, after conversion
-// to bf16, exactly the B-operand layout of the second, so P never leaves registers; the
-// contraction index kv is enumerated in the accumulator's order on both operands.
-//   exact:  Kx = K tile,  Qx = Q,    contraction over d channels
-//   distr:  Kx = K_f tile (Sec. 3.2 fusion: sum of the group's K channels, built once per
-//           (Q block, K tile) by all waves together: packed half adds in registers on pieces of
-//           a transposed half-precision copy of K, result in LDS), Qx = Q_r (sampling: the
-//           group's first channel in sorted order, gathered once per Q block), contraction over
-//           n_groups = d / G*, on the f16 matrix path. The grouping itself (Sec. 3.2 LSH, sort,
-//           groups) is either read from a table or computed by the workgroup in its prologue.
-// Online softmax (reference max, row sum, rescaled accumulator) follows the block-wise scheme of
-// Sec. 2.2.2 in the exp2 domain.
-//
-// Pipeline (one barrier per tile): K (exact) and V tiles reach LDS by direct global->LDS loads
-// two tiles (K) / one tile (V) ahead, the K^T pieces of the fusion reach registers one tile
-// ahead of their use; while the vector ALUs exponentiate tile i the matrix pipe computes the
-// scores of tile i+1; P.V of tile i runs beside the row maximum of tile i+1.
-#include <type_traits>
-
+// Entry of the bf16 attention kernels: which shapes are built, and the dispatch over the K/V tile
+// size (one translation unit per tile size: attn_bf16_bc32/64/128.hip, kernel in attn_bf16_impl.h).
 #include "da_common.h"
 
 namespace da {
 
-namespace {
-
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-typedef _Float16 f16;
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-
-// Largest finite half; sampled queries and fused keys of the distr path are clamped to it.
-constexpr float kHalfMax = 65504.0f;
-__device__ inline f16 to_half_sat(float x) { return (f16)__builtin_amdgcn_fmed3f(x, -kHalfMax, kHalfMax); }
-
-__device__ inline f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-__device__ inline f32x16 mfma_32x32x16(f16x8 a, f16x8 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
-}
-
-// Two transposing LDS reads (ds_read_b64_tr_b16): within each group of 16 lanes, lane i
-// receives element (i % 4) of the 8-byte chunks addressed by lanes 4j + i/4, j = 0..3.
-template <typename V8>
-__device__ inline V8 lds_read_tr_pair(const void* p0, const void* p1) {
-  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p0);
-  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p1);
-  s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-  return __builtin_bit_cast(V8, r);
-}
-
-// Exchange between the wave halves: v_permlane32_swap swaps the upper 32 lanes of its first
-// operand with the lower 32 lanes of its second; fed the same value twice it leaves, in every
-// lane, the values of lanes l % 32 (first operand) and l % 32 + 32 (second operand). Written as
-// inline asm with both registers read-write: the builtin's second result was dropped by the
-// compiler when both inputs were the same value. The s_nop covers the VALU-write -> permlane
-// read hazard, which the compiler cannot see inside an asm block.
-__device__ inline void half_pair(float x, float& lo, float& hi) {
-  float a = x, b = x;
-  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
-  lo = a;
-  hi = b;
-}
-__device__ inline float half_swap_max(float x) {
-  float lo, hi;
-  half_pair(x, lo, hi);
-  return fmaxf(lo, hi);
-}
-__device__ inline float half_swap_sum(float x) {
-  float lo, hi;
-  half_pair(x, lo, hi);
-  return lo + hi;
-}
-
-// Swizzle of the 32-byte segments of a tile that is read with transposing accesses
-// (ds_read_b64_tr_b16): the LDS serves 32 lanes of such a read per cycle, which address the rows
-// r..r+3 (r a multiple of 4) at two adjacent 32-byte segments, 4 lanes x 8 bytes per row and
-// segment. v_swizzle spreads those 4 rows x 2 segments over all 64 banks (no conflict cycles in
-// the hardware counters): with 256-byte rows the row picks one of four segment pairs, with
-// 128-byte rows two consecutive rows already sit in opposite bank halves and only rows of equal
-// parity need separating.
-template <int ROW_BYTES>
-__device__ inline int v_swizzle(int row) {
-  static_assert(ROW_BYTES == 256 || ROW_BYTES == 128, "row length");
-  return ROW_BYTES == 256 ? ((row & 3) << 1) : (row & 2);
-}
-// The fused tile K_f^T (128-byte rows) keeps a swizzle that leaves a two-way conflict on its
-// transposing reads: those reads are limited by the return path, not by the banks (same
-// throughput in a micro-benchmark), and the kernels built with the conflict-free form (row & 2)
-// were measured within 1 % at d = 128 and 4 % slower at d = 64.
-__device__ inline int kf_swizzle(int row) { return (row >> 1) & 3; }
-
-// KRED: contraction length of the score product (a multiple of the MFMA step, 16). NG: number of
-// channel groups; smaller than KRED only for n_groups 4 and 8, whose operands are zero-padded to 16.
-template <int D, int BR, int KRED, bool DISTR, int NG = KRED>
-struct Cfg {
-  static constexpr int NW = BR / 32;              // wavefronts per workgroup
-  static constexpr int T = NW * 64;               // threads
-  static constexpr int G = D / NG;                // channels per group
-  static constexpr int CH = D / 8;                // 16-byte chunks per row
-  static constexpr int CPT = kBc * CH / T;        // chunks each thread stages per tile
-  // LDS layouts.
-  //  * V tiles, and K tiles of the exact path, arrive by direct global->LDS loads (each
-  //    wave-level load drops 64 x 16 bytes contiguously), so rows are unpadded (D*2 bytes) and
-  //    bank conflicts are avoided by swizzling where a 16-byte chunk sits inside its row:
-  //      K (read with 16-byte accesses, 16 lanes = 16 rows at one logical chunk):
-  //          chunk' = chunk ^ (row & 15)            (D = 128: 16 chunks per row)
-  //          chunk' = chunk ^ ((row >> 1) & 7)      (D = 64: 8 chunks per row, two rows per 256 B)
-  //      V (read with transposing 8-byte accesses; the LDS serves 32 lanes per cycle, which
-  //      address 4 rows x 2 adjacent 32-byte segments and must cover all 256 bytes of banks):
-  //          32-byte segment' = segment ^ 2*(row & 3)       (D = 128: 8 segments per row)
-  //          32-byte segment' = segment ^ (row & 2)         (D = 64: 4 segments per row, rows of
-  //                                                          opposite parity sit in opposite bank halves)
-  //    The loading lane fetches the global chunk that belongs at its LDS position.
-  //  * distr path: the keys arrive transposed and in half precision (K^T in global memory, one
-  //    row of 64 keys = 128 bytes per channel and tile, written once per forward by the key
-  //    pre-pass). Only the fused tile K_f^T (one 128-byte row per group) lives in LDS: written by
-  //    the waves, read back with transposing accesses, segments swizzled by kf_swizzle.
-  static constexpr int ROWB = D * 2;              // bytes of an unpadded K / V row
-  static constexpr int TILEB = kBc * ROWB;        // bytes of an unpadded 64-row tile
-  static constexpr int KTROWB = kBc * 2;          // bytes of a K^T / K_f^T row (64 keys)
-  static constexpr int KX_BYTES = DISTR ? KRED * KTROWB : TILEB;   // one Kx buffer: K_f^T or K
-  static constexpr int FUSE_OUT = (NG * 8 + T - 1) / T;     // 16-byte fused outputs per thread and tile
-  static constexpr int KSTEPS = KRED / 16;        // MFMA steps of the score product
-};
-
-// Lazy reference maximum. A row keeps its reference until one of its scores runs more than kTau
-// (log2 units) ahead of it: P is then at most 2^kTau, numerator and denominator share the
-// reference, so the result is the same ratio, and the accumulator rescale (one multiply per
-// accumulator register) almost never runs. The test needs no row maximum: a lane's row sum over
-// the 32 keys it owns in a tile exceeds kSumTrigger only if one of them exceeds 2^kTau (an
-// overflowed or NaN sum fails the comparison too), and the sum is needed anyway.
-constexpr float kTau = 8.0f;
-constexpr float kSumTrigger = 32.0f * 256.0f;   // 32 keys per lane and tile, each at most 2^kTau
-
-template <int D, int BR, int KRED, bool DISTR, int NG>
-__global__ __launch_bounds__(BR * 2, 2) void attn_bf16_kernel(
-    const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-    bf16* __restrict__ o, const uint8_t* __restrict__ perm, const f16* __restrict__ kt, int Npad,
-    int H, int Hkv, int N, int Nk, int Tq, int causal, float scale_log2e, int total_units, int n_planes,
-    int gray_mode, uint64_t lsh_seed) {
-  using C = Cfg<D, BR, KRED, DISTR, NG>;
-  using kx8 = typename std::conditional<DISTR, f16x8, bf16x8>::type;
-  // Kx and V tiles are double-buffered: while tile i multiplies, tile i+1 (V) / i+2 (K) lands.
-  // Each buffer is a separate LDS object: the compiler can then tell that the operand reads of
-  // one buffer do not depend on the direct loads still in flight into the other.
-  __shared__ __attribute__((aligned(1024))) char kx_lds0[C::KX_BYTES];
-  __shared__ __attribute__((aligned(1024))) char kx_lds1[C::KX_BYTES];
-  __shared__ __attribute__((aligned(1024))) char v_lds0[C::TILEB];
-  __shared__ __attribute__((aligned(1024))) char v_lds1[C::TILEB];
-  auto kx_buf = [&](int par) -> char* { return par ? kx_lds1 : kx_lds0; };
-  auto v_buf = [&](int par) -> char* { return par ? v_lds1 : v_lds0; };
-  // The block's permutation is only needed while the prologue builds the sampled-query operands
-  // and the fusion offsets: it borrows the head of the second V buffer, which receives its
-  // first tile in the first loop iteration (after the prologue's barriers).
-  uint8_t* perm_lds = (uint8_t*)v_lds1;
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int lq = lane & 31;   // query row of this lane inside the wave's 32 rows
-  const int hh = lane >> 5;   // which half of each 8-wide contraction chunk this lane feeds
-
-  // Workgroup -> (batch*head, Q block). Consecutive workgroup ids go round-robin over the 8 XCDs.
-  int unit = blockIdx.x;
-  int bh, t;
-  if (causal == 2) {
-    // Causal blocks differ up to Tq-fold in length. When (nearly) all of them are resident at
-    // once, head after head would leave whole compute units with only long or only short
-    // blocks: take them longest first over all heads, so that every round of the dispatcher
-    // spreads one length class over the chip and the short blocks fill the slots that free up
-    // last. With a head count that is a multiple of 8 a head still stays on one XCD.
-    const int n_bh = total_units / Tq;
-    t = Tq - 1 - unit / n_bh;
-    bh = unit % n_bh;
-  } else {
-    // Each XCD walks a contiguous range of units, so the Q blocks of one head run together
-    // and share that XCD's L2 for K and V; the causal blocks of a head longest first.
-    if ((total_units & 7) == 0) unit = (blockIdx.x & 7) * (total_units >> 3) + (blockIdx.x >> 3);
-    bh = unit / Tq;
-    t = unit % Tq;
-    if (causal) t = Tq - 1 - t;
-  }
-  const int b = bh / H, h = bh % H;
-  const int hk = h / (H / Hkv);
-  const int r0 = t * BR;
-
-  const bf16* qh = q + (size_t)bh * N * D;
-  const bf16* kh = k + (size_t)(b * Hkv + hk) * Nk * D;
-  const bf16* vh = v + (size_t)(b * Hkv + hk) * Nk * D;
-  // N queries against Nk keys; under the causal mask the last query is aligned with the last
-  // key: key n is visible to query i iff n <= i + shift.
-  const int shift = Nk - N;
-
-  const int qw0 = r0 + wave * 32;              // first query row of this wave
-  const int q_abs = qw0 + lq;                  // this lane's query row
-  const int q_ld = min(q_abs, N - 1);          // ragged block: load a valid row, never store it
-
-  if constexpr (DISTR) {
-    if constexpr (NG < KRED) {
-      // Rows NG..KRED-1 of K_f^T pad the contraction: zeroed once, the fusion never writes them.
-      // (They lie behind the 2*D*4 bytes the LSH stage below borrows from the first buffer:
-      // 2*D*4 <= NG*128 because a group has at most 16 channels.)
-      static_assert(2 * D * 4 <= NG * C::KTROWB, "padding rows and LSH scratch are disjoint");
-      const f16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-      for (int i = NG * C::KTROWB / 16 + tid; i < C::KX_BYTES / 16; i += C::T) {
-        ((f16x8*)kx_lds0)[i] = zero;
-        ((f16x8*)kx_lds1)[i] = zero;
-      }
-    }
-    if (perm != nullptr) {
-      const size_t pbase = ((size_t)bh * Tq + t) * D;
-      // D is a power of two: an out-of-range entry of a caller's table cannot index past a row
-      for (int i = tid; i < D; i += C::T) perm_lds[i] = perm[pbase + i] & (D - 1);
-    } else {
-      // ---- LSH hash-and-group of this Q block inside the workgroup (Sec. 3.2, 3.3) -------------
-      // Same arithmetic as the stand-alone LSH kernel (float, one fused multiply-add per row,
-      // rows ascending, from +0), so the table equals that kernel's bit for bit; here it costs
-      // no launch, no table in HBM, and runs while the CU's other workgroup keeps the matrix
-      // pipes busy. Up to 16 projections: R[row][16] borrows the first V buffer (8 KB), the
-      // codes and hashes borrow the first Kx buffer; both are filled only after the barriers below.
-      constexpr int NPG = C::T / D;             // threads per channel
-      constexpr int PPT = 16 / NPG;             // projections per thread: pg*PPT .. pg*PPT+PPT-1
-      static_assert(C::T % D == 0 && BR * 16 * 4 <= C::TILEB && 2 * D * 4 <= C::KX_BYTES, "LSH scratch fits");
-      float* R_lds = (float*)v_lds0;
-      uint32_t* code_lds = (uint32_t*)kx_lds0;
-      uint32_t* hash_lds = code_lds + D;
-      for (int i = tid; i < BR * 16; i += C::T)
-        R_lds[i] = (i & 15) < n_planes ? hyperplane_entry(lsh_seed, (uint32_t)(i & 15), (uint32_t)(i >> 4)) : 0.0f;
-      if (tid < D) code_lds[tid] = 0;
-      __syncthreads();
-      const int c = tid % D, pg = tid / D;
-      const int rows = min(BR, N - r0);
-      const bf16* qcol = qh + (size_t)r0 * D + c;
-      float acc[PPT];
-#pragma unroll
-      for (int j = 0; j < PPT; ++j) acc[j] = 0.0f;
-      // 16 column loads in flight per thread: with two workgroups per CU nothing else hides
-      // their latency here (the stand-alone kernel, at 8 workgroups per CU, does with 4).
-#pragma unroll 16
-      for (int r = 0; r < rows; ++r) {
-        const float x = (float)qcol[(size_t)r * D];
-#pragma unroll
-        for (int j = 0; j < PPT; ++j) acc[j] = __builtin_fmaf(x, R_lds[r * 16 + pg * PPT + j], acc[j]);
-      }
-      uint32_t bits = 0;
-#pragma unroll
-      for (int j = 0; j < PPT; ++j) {
-        const int pl = pg * PPT + j;
-        if (pl < n_planes && acc[j] > 0.0f) bits |= 1u << (n_planes - 1 - pl);   // projection 0 = top bit
-      }
-      if (NPG == 1) code_lds[c] = bits;
-      else if (bits) atomicOr(&code_lds[c], bits);
-      __syncthreads();
-      if (tid < D) hash_lds[tid] = lsh_hash_of_code(code_lds[tid], gray_mode);
-      __syncthreads();
-      if (tid < D) {   // rank by counting = stable ascending sort; perm = inverse of the rank
-        const uint32_t mine = hash_lds[tid];
-        int rank = 0;
-        for (int o = 0; o < D; ++o) {
-          const uint32_t other = hash_lds[o];
-          rank += (other < mine || (other == mine && o < tid)) ? 1 : 0;
-        }
-        perm_lds[rank] = (uint8_t)tid;
-      }
-    }
-    __syncthreads();
-  }
-
-  // ---- Q operands, held for the whole inner loop ------------------------------------------
-  // distr: the reduced product runs on the f16 matrix path. A bf16 value converts to half
-  // exactly (8 vs 11 significand bits) inside half's exponent range, and the fused keys, rounded
-  // to half from the sum of such values, keep 3 more bits than bf16 would: with bf16 K_f the logit error
-  // on inputs with heavy-tailed channel scales exceeds what the output tolerance allows.
-  // distr: Q_r carries the factor softmax_scale * log2(e), rounded once more to half (11 bits:
-  // the rounding is 8 times finer than the bf16 grid the inputs come from). The score
-  // accumulators then hold the exponent of 2 directly. The exact path keeps Q as it is: scaling
-  // and re-rounding to bf16 would cost accuracy on rows with close top scores, so there the
-  // factor is applied to the float scores, one fused multiply-add per score.
-  kx8 qop[C::KSTEPS];
-  if constexpr (DISTR) {
-    const bf16* qrow = qh + (size_t)q_ld * D;
-#pragma unroll
-    for (int s = 0; s < C::KSTEPS; ++s) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (NG == KRED || 16 * s + 8 * hh + j < NG)
-          qop[s][j] = to_half_sat((float)qrow[perm_lds[(16 * s + 8 * hh + j) * C::G]] * scale_log2e);
-        else
-          qop[s][j] = (f16)0.0f;   // padding of the contraction: no group there
-    }
-  } else {
-#pragma unroll
-    for (int s = 0; s < C::KSTEPS; ++s)
-      qop[s] = *(const bf16x8*)(qh + (size_t)q_ld * D + 16 * s + 8 * hh);
-  }
-  // The Q operands must have landed before the loop starts: otherwise the compiler's wait-count
-  // bookkeeping carries "Q loads pending" into the loop and the MFMAs also wait for the K/V
-  // prefetch of later tiles.
-#pragma unroll
-  for (int s = 0; s < C::KSTEPS; ++s) asm volatile("" : "+v"(qop[s]));
-
-  // ---- fusion bookkeeping, fixed for the Q block ------------------------------------------------
-  // Fused output u of this thread is the 16-byte piece (8 keys) number idx % 8 of group
-  // idx / 8, idx = tid + u*T: it sums the same piece of the group's G channel rows of K^T
-  // (f_src: byte offset of the piece inside the head's K^T, tile 0) and lands in row idx / 8 of
-  // K_f^T at the swizzled position (f_dst).
-  int f_src[DISTR ? C::FUSE_OUT : 1][DISTR ? C::G : 1];
-  int f_dst[DISTR ? C::FUSE_OUT : 1];
-  if constexpr (DISTR) {
-#pragma unroll
-    for (int u = 0; u < C::FUSE_OUT; ++u) {
-      const int idx = min(tid + u * C::T, NG * 8 - 1);
-      const int j = idx >> 3, c8 = idx & 7;
-#pragma unroll
-      for (int g = 0; g < C::G; ++g)
-        f_src[u][g] = perm_lds[j * C::G + g] * Npad * 2 + c8 * 16;
-      f_dst[u] = j * C::KTROWB + ((((c8 >> 1) ^ kf_swizzle(j)) << 1) | (c8 & 1)) * 16;
-    }
-  }
-
-  const int n_end = causal ? min(Nk, r0 + BR + shift) : Nk;
-  const int n_tiles = (n_end + kBc - 1) / kBc;
-  // tiles [0, n_full) need no masking for any row of the block
-  const int n_full = causal ? min(r0 + shift, Nk) / kBc : Nk / kBc;
-
-  // ---- tile loads: global -> LDS ---------------------------------------------------------------
-  // K and V rows are fetched through buffer descriptors: the per-lane byte offset inside a
-  // tile is fixed, the tile advances through the scalar offset, and rows past the end of the
-  // head read as zero (hardware range check), so a tile costs no address arithmetic.
-  const unsigned head_bytes = (unsigned)Nk * D * 2;
-  const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kh, 0, head_bytes, 0x00020000);
-  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)vh, 0, head_bytes, 0x00020000);
-
-  // Direct global->LDS tile loads. Wave-level load j of this wave fills the 1 KB block
-  // j*NW + wave of the tile; lane i owns the 16 bytes at offset 16*i of that block, i.e. LDS
-  // row (slot / CH), chunk position (slot % CH) with slot = 64*block + i, and fetches the global
-  // chunk the swizzle assigns to that position.
-  int dma_k[DISTR ? 1 : C::CPT], dma_v[C::CPT];
-#pragma unroll
-  for (int j = 0; j < C::CPT; ++j) {
-    const int slot = (j * C::NW + wave) * 64 + lane;
-    const int row = slot / C::CH, pc = slot % C::CH;
-    if constexpr (!DISTR) dma_k[j] = row * C::ROWB + (pc ^ (D == 128 ? (row & 15) : ((row >> 1) & 7))) * 16;
-    const int lseg = (pc >> 1) ^ v_swizzle<C::ROWB>(row);
-    dma_v[j] = row * C::ROWB + (lseg * 2 + (pc & 1)) * 16;
-  }
-  typedef __attribute__((address_space(3))) void lds_void;
-  auto dma_blocks = [&](auto n_c, __amdgpu_buffer_rsrc_t rsrc, int soff, const int* voff, char* dst) {
-#pragma unroll
-    for (int j = 0; j < decltype(n_c)::value; ++j)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(dst + (j * C::NW + wave) * 1024), 16,
-                                               voff[j], soff, 0, 0);
-  };
-  auto dma_tile = [&](__amdgpu_buffer_rsrc_t rsrc, int tile, const int* voff, char* dst) {
-    dma_blocks(std::integral_constant<int, C::CPT>(), rsrc, tile * C::TILEB, voff, dst);
-  };
-  auto dma_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
-
-  // distr: K^T of this kv head, [D channel rows][Npad keys] half.
-  const __amdgpu_buffer_rsrc_t kt_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)(DISTR ? kt + (size_t)(b * Hkv + hk) * D * Npad : nullptr), 0, (unsigned)D * Npad * 2, 0x00020000);
-  // ---- fusion (Sec. 3.2): K_f^T[j][n] = sum over the group's channels c of K^T[c][n], eight keys
-  // at a time with packed half adds (for G* = 2 the sum of two bf16-valued halves is rounded to
-  // half once; larger groups add one channel after the other). Every thread loads the 16-byte
-  // pieces it sums straight from K^T in global memory (8 lanes cover one 128-byte channel row)
-  // one tile iteration before it adds them, so the LDS only sees K_f^T (8-16 KB per tile): with
-  // the raw tile staged in LDS and summed from there (direct load, 16 KB read, K_f^T written)
-  // the kernel was bound by LDS traffic and 2-12 % slower.
-    typedef f16x8 Pieces[DISTR ? C::FUSE_OUT : 1][DISTR ? C::G : 1];
-  Pieces piece;   // the set the main loop carries from one iteration to the next
-  auto load_pieces = [&](int tile, Pieces& pc) {
-    if constexpr (DISTR) {
-#pragma unroll
-      for (int u = 0; u < C::FUSE_OUT; ++u)
-#pragma unroll
-        for (int g = 0; g < C::G; ++g)
-          pc[u][g] = __builtin_bit_cast(f16x8, __builtin_amdgcn_raw_buffer_load_b128(kt_rsrc, f_src[u][g], tile * C::KTROWB, 0));
-    }
-  };
-  auto fuse_pieces = [&](int buf, const Pieces& pc) {   // loaded pieces -> K_f^T in kx_buf(buf)
-    if constexpr (DISTR) {
-      char* dst = kx_buf(buf);
-#pragma unroll
-      for (int u = 0; u < C::FUSE_OUT; ++u) {
-        f16x8 acc = pc[u][0];
-#pragma unroll
-        for (int g = 1; g < C::G; ++g) acc += pc[u][g];
-        if (NG * 8 % C::T == 0 || tid + u * C::T < NG * 8) *(f16x8*)(dst + f_dst[u]) = acc;
-      }
-    }
-  };
-
-  // ---- accumulators and softmax state ---------------------------------------------------------
-  f32x16 oacc[D / 32];
-#pragma unroll
-  for (int mb = 0; mb < D / 32; ++mb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) oacc[mb][i] = 0.0f;
-  // Softmax state of this lane's query row, in the exp2 domain: the negated reference maximum
-  // and the row sum relative to it. distr: the negated reference also sits in all 16 registers
-  // of neg_ref, which the first MFMA of every score chain takes as its addend, so the
-  // accumulators come out as (scaled score - m_ref) and go straight into exp2.
-  constexpr bool PRESCALED = DISTR;
-  float nref = 0.0f;
-  f32x16 neg_ref;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) neg_ref[i] = 0.0f;
-  float l_run = 0.0f;        // over this lane's half of the keys
-
-  // LDS byte offsets of this lane's operands inside a buffer.
-  // Score product, A operand (exact): row lq (+32 per key block), logical chunk 2*s + hh.
-  int ka_off[DISTR ? 4 : C::KSTEPS];
-  if constexpr (DISTR) {
-    // K_f^T is read like V: lane addresses group row 8*hh + 4*half + (lane%16)/4 (+16*s), 32-byte
-    // segment 2*mb + (lane/16)%2 (keys 32*mb + 16*((lane/16)%2) ..), 8-byte piece lane%4.
-    const int r4 = (lane & 15) >> 2;
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf)
-        ka_off[mb * 2 + hf] = (8 * hh + 4 * hf + r4) * C::KTROWB +
-                              ((2 * mb + ((lane >> 4) & 1)) ^ kf_swizzle(4 * hf + r4)) * 32 + 8 * (lane & 3);
-  } else {
-#pragma unroll
-    for (int s = 0; s < C::KSTEPS; ++s)
-      ka_off[s] = lq * C::ROWB + ((2 * s + hh) ^ (D == 128 ? (lq & 15) : ((lq >> 1) & 7))) * 16;
-  }
-  // P.V, A operand via transposing reads: lane addresses row 4*hh + (lane%16)/4 (+8, +16*tt),
-  // logical 32-byte segment 2*mb + (lane/16)%2, 8-byte piece lane%4 of it.
-  int va_off[D / 32];
-  {
-    const int row_l = 4 * hh + ((lane & 15) >> 2);
-    const int swz = v_swizzle<C::ROWB>(row_l);
-#pragma unroll
-    for (int mb = 0; mb < D / 32; ++mb)
-      va_off[mb] = row_l * C::ROWB + ((2 * mb + ((lane >> 4) & 1)) ^ swz) * 32 + 8 * (lane & 3);
-  }
-
-  // S^T = Kx . Qx^T for the Kx tile in buffer `buf`: register i of block mb holds key
-  // 32*mb + 8*(i/4) + 4*hh + i%4 of the tile.
-  auto qk = [&](int buf, f32x16 (&sacc)[2]) {
-    const char* base = kx_buf(buf);
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-#pragma unroll
-      for (int s = 0; s < C::KSTEPS; ++s) {
-        kx8 a;
-        if constexpr (DISTR)
-          a = lds_read_tr_pair<kx8>(base + ka_off[mb * 2] + s * 16 * C::KTROWB,
-                                    base + ka_off[mb * 2 + 1] + s * 16 * C::KTROWB);
-        else
-          a = *(const kx8*)(base + ka_off[s] + mb * 32 * C::ROWB);
-        if (s == 0) {
-          if constexpr (PRESCALED) sacc[mb] = neg_ref;
-          else
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[mb][i] = 0.0f;
-        }
-        sacc[mb] = mfma_32x32x16(a, qop[s], sacc[mb]);
-      }
-    }
-  };
-
-  // Causal / ragged-tail mask of the scores of tile `tile`.
-  auto apply_mask = [&](int tile, f32x16 (&sc)[2]) {
-    const int lim = causal ? min(q_abs + shift, Nk - 1) : Nk - 1;  // last visible key of this row
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        int kv = tile * kBc + 32 * mb + 8 * (i >> 2) + 4 * hh + (i & 3);
-        if (kv > lim) sc[mb][i] = -INFINITY;
-      }
-  };
-  // Row maximum of a tile's scores (relative to the current reference), the same in both lanes
-  // of a row.
-  auto tile_max = [&](const f32x16 (&sc)[2]) -> float {
-    float mt = sc[0][0];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sc[mb][i]);
-    mt = half_swap_max(mt);
-    return PRESCALED ? mt : __builtin_fmaf(mt, scale_log2e, nref);
-  };
-  // P = exp2(scores) rounded to bf16, as the B operands of P.V; returns this lane's row sum. The
-  // sum is taken over the rounded P, the values P.V really uses (one bf16 dot product with (1, 1)
-  // per register pair): numerator and denominator then carry the same rounding, which cancels
-  // for rows dominated by few keys.
-  auto exp_tile = [&](const f32x16 (&sc)[2], bf16x8 (&pop)[4]) -> float {
-    const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
-    float rs0 = 0.0f, rs1 = 0.0f;
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int i = 0; i < 16; i += 2) {
-        float x0 = sc[mb][i], x1 = sc[mb][i + 1];
-        if constexpr (!PRESCALED) {
-          x0 = __builtin_fmaf(x0, scale_log2e, nref);
-          x1 = __builtin_fmaf(x1, scale_log2e, nref);
-        }
-        bf16x2 pr = {(bf16)__builtin_amdgcn_exp2f(x0), (bf16)__builtin_amdgcn_exp2f(x1)};
-        pop[mb * 2 + (i >> 3)][i & 7] = pr[0];
-        pop[mb * 2 + (i >> 3)][(i & 7) + 1] = pr[1];
-        if (i & 2) rs1 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs1, false);
-        else rs0 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs0, false);
-      }
-    return rs0 + rs1;
-  };
-  // The reference of this lane's row moves up by `delta`: everything that is relative to it
-  // follows (row sum, output accumulator, the scores already computed against the old one).
-  auto shift_reference = [&](float delta, auto rescale_c, f32x16 (&sc)[2], auto next_c, f32x16 (&sn)[2]) {
-    nref -= delta;
-    if constexpr (PRESCALED) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) neg_ref[i] -= delta;
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          sc[mb][i] -= delta;
-          if constexpr (decltype(next_c)::value) sn[mb][i] -= delta;
-        }
-    }
-    if constexpr (decltype(rescale_c)::value) {
-      const float alpha = __builtin_amdgcn_exp2f(-delta);
-      l_run *= alpha;
-#pragma unroll
-      for (int mb = 0; mb < D / 32; ++mb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[mb][i] *= alpha;
-    }
-  };
-
-  // One tile `it`, whose scores `sc` are masked and relative to the row's reference:
-  //   scores of tile it+1 into `sn` (matrix pipe)  ||  exp2, bf16 P, row sum of `sc` (vector ALUs)
-  //   the rare reference move, then O^T += V^T . P^T for tile it (matrix pipe), the mask of
-  //   tile it+1 where it needs one, one barrier.
-  auto body = [&](auto mask_next_c, auto next_c, int it, int par, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
-    constexpr bool HAS_NEXT = decltype(next_c)::value;
-    // The buffers these loads fill were last read in the previous iteration, which every wave
-    // has left (barrier): K(it+2) replaces K(it), V(it+1) replaces V(it-1).
-    if constexpr (HAS_NEXT) {
-      // distr: the pieces of K^T(it+2), loaded during the previous iteration, are summed now
-      // into the buffer K_f^T(it) has left, and the loads of K^T(it+3) take their registers.
-      // Nothing in this iteration depends on the fusion: it runs beside the MFMAs.
-      if constexpr (DISTR) {
-        fuse_pieces(par, piece);       // K^T(it+2), loaded during the previous iteration
-        load_pieces(it + 3, piece);
-      }
-      if constexpr (!DISTR) dma_tile(k_rsrc, it + 2, dma_k, kx_buf(par));
-      dma_tile(v_rsrc, it + 1, dma_v, v_buf(par ^ 1));
-    }
-    if constexpr (HAS_NEXT) qk(par ^ 1, sn);
-    bf16x8 pop[4];
-    float rs = exp_tile(sc, pop);
-    if (__builtin_amdgcn_ballot_w64(!(rs <= kSumTrigger)) != 0) {
-      // Some row of this wave met a score more than kTau above its reference: such rows take the
-      // tile's maximum as their new reference and the tile's P is computed again.
-      const float mt = tile_max(sc);
-      shift_reference(mt > kTau ? mt : 0.0f, std::true_type(), sc, next_c, sn);
-      rs = exp_tile(sc, pop);
-    }
-    l_run += rs;
-    // ---- O^T += V^T . P^T: step tt covers keys 16*tt + {8*(j/4) + 4*hh + j%4} of the tile,
-    // i.e. V rows 16*tt + 4*hh + 0..3 and 16*tt + 8 + 4*hh + 0..3.
-    const char* vb = v_buf(par);
-#pragma unroll
-    for (int tt = 0; tt < 4; ++tt) {
-#pragma unroll
-      for (int mb = 0; mb < D / 32; ++mb) {
-        const char* p0 = vb + va_off[mb] + 16 * tt * C::ROWB;
-        bf16x8 a = lds_read_tr_pair<bf16x8>(p0, p0 + 8 * C::ROWB);
-        oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pop[tt], oacc[mb], 0, 0, 0);
-      }
-    }
-    if constexpr (HAS_NEXT) {
-      if constexpr (decltype(mask_next_c)::value) apply_mask(it + 1, sn);
-      dma_wait();              // this wave's direct loads have landed
-    }
-    __syncthreads();
-  };
-
-  // ---- prologue: tiles 0 (K, V) and 1 (K) into LDS, scores of tile 0 ---------------------------
-  dma_tile(v_rsrc, 0, dma_v, v_lds0);
-  if constexpr (DISTR) {
-    Pieces first;        // tiles 0 and 1 travel together (registers are plentiful before the loop)
-    load_pieces(0, first);
-    load_pieces(1, piece);
-    fuse_pieces(0, first);
-    fuse_pieces(1, piece);
-    load_pieces(2, piece);
-    dma_wait();          // V(0) has landed (and, with it, the pieces of tile 2)
-    __syncthreads();     // K_f^T(0), K_f^T(1) and V(0) are visible
-  } else {
-    dma_tile(k_rsrc, 0, dma_k, kx_lds0);
-    if (n_tiles > 1) dma_tile(k_rsrc, 1, dma_k, kx_lds1);
-    dma_wait();
-    __syncthreads();
-  }
-
-  const std::true_type yes;
-  const std::false_type no;
-  f32x16 s0[2], s1[2];
-  qk(0, s0);             // against the initial reference 0
-  apply_mask(0, s0);
-  // The first tile sets the reference to its row maximum (key 0 is visible to every row, so the
-  // maximum is finite); nothing has been accumulated yet, so nothing is rescaled.
-  shift_reference(tile_max(s0), no, s0, no, s1);
-  // The first iteration refills the buffer of tile 0 (direct load of K(2), or the fusion of
-  // K_f^T(2)): every wave must have read its scores of tile 0 out of it first.
-  __syncthreads();
-
-  // Tile it+1 needs no mask while it+1 < n_full. The main loop is unrolled by two so that the
-  // two score register sets swap roles without copies.
-  int it = 0;
-  for (; it + 2 < n_full; it += 2) {
-    body(no, yes, it, 0, s0, s1);
-    body(no, yes, it + 1, 1, s1, s0);
-  }
-  for (; it < n_tiles - 1; ++it) {   // at most two unmasked leftovers plus the masked tiles
-    body(yes, yes, it, it & 1, s0, s1);
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) s0[mb] = s1[mb];
-  }
-  body(no, no, it, it & 1, s0, s1);
-
-  // ---- epilogue: O = O_acc / l, bf16, 8-byte stores ---------------------------------------------
-  const float l_tot = half_swap_sum(l_run);
-  const float inv = 1.0f / l_tot;
-  if (q_abs < N) {
-    bf16* orow = o + ((size_t)bh * N + q_abs) * D;
-#pragma unroll
-    for (int mb = 0; mb < D / 32; ++mb)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        bf16x4 pk;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) pk[j] = (bf16)(oacc[mb][4 * i4 + j] * inv);
-        *(bf16x4*)(orow + 32 * mb + 8 * i4 + 4 * hh) = pk;
-      }
-  }
-}
-
-template <int D, int BR, int KRED, bool DISTR, int NG = KRED>
-hipError_t launch_one(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
-                      const void* kt, const Problem& pb, hipStream_t stream) {
-  const int Tq = (pb.N + BR - 1) / BR;
-  const long long units = (long long)pb.B * pb.H * Tq;
-  const float scale_log2e = pb.scale * 1.4426950408889634f;
-  // causal_mode 2 = blocks issued longest first over all heads (see the kernel): for problems
-  // of up to 8 workgroups per compute unit, where load balance matters more than L2 locality
-  // (with more blocks the dispatcher balances by itself and the head-major order fetches half
-  // as many bytes from HBM).
-  const int causal_mode = pb.causal ? (units <= 8 * 256 ? 2 : 1) : 0;
-  hipLaunchKernelGGL((attn_bf16_kernel<D, BR, KRED, DISTR, NG>), dim3((unsigned)units), dim3(BR * 2), 0,
-                     stream, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, perm, (const f16*)kt,
-                     (pb.Nk + kBc - 1) / kBc * kBc, pb.H, pb.Hkv, pb.N, pb.Nk, Tq, causal_mode, scale_log2e, (int)units,
-                     pb.n_planes, pb.gray_mode, pb.seed);
-  return hipGetLastError();
-}
-
-template <int D, int BR>
-hipError_t dispatch_kred(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
-                         const void* kt, const Problem& pb, int distr, hipStream_t stream) {
-  if (!distr) return launch_one<D, BR, D, false>(q, k, v, o, perm, kt, pb, stream);
-  switch (pb.n_groups) {   // n_groups = d (groups of one channel) is the exact product: dispatched by the caller
-    case 4:                // fewer groups than one MFMA step: contraction zero-padded to 16
-      if constexpr (D == 64) return launch_one<D, BR, 16, true, 4>(q, k, v, o, perm, kt, pb, stream);
-      return hipErrorInvalidValue;
-    case 8: return launch_one<D, BR, 16, true, 8>(q, k, v, o, perm, kt, pb, stream);
-    case 16: return launch_one<D, BR, 16, true>(q, k, v, o, perm, kt, pb, stream);
-    case 32: return launch_one<D, BR, 32, true>(q, k, v, o, perm, kt, pb, stream);
-    case 64:
-      if constexpr (D == 128) return launch_one<D, BR, 64, true>(q, k, v, o, perm, kt, pb, stream);
-      [[fallthrough]];
-    default: return hipErrorInvalidValue;
-  }
-}
-
-}  // namespace
+hipError_t launch_attn_bf16_bc32(const void*, const void*, const void*, void*, const uint8_t*, const void*,
+                                 const Problem&, int, hipStream_t);
+hipError_t launch_attn_bf16_bc64(const void*, const void*, const void*, void*, const uint8_t*, const void*,
+                                 const Problem&, int, hipStream_t);
+hipError_t launch_attn_bf16_bc128(const void*, const void*, const void*, void*, const uint8_t*, const void*,
+                                  const Problem&, int, hipStream_t);
 
 bool attn_bf16_supported(const Problem& pb, int distr) {
   if (pb.d != 64 && pb.d != 128) return false;
-  if (pb.Br != 64 && pb.Br != 128) return false;
+  if (pb.Br != 64 && pb.Br != 128 && pb.Br != 256) return false;
+  if (pb.Bc != 32 && pb.Bc != 64 && pb.Bc != 128) return false;
   if (distr) {
-    const int kr = pb.n_groups;   // groups of up to 16 channels (G* in {1, 2, 4, 8, 16}, Sec. 3.2 and Table 4)
-    if (kr != 4 && kr != 8 && kr != 16 && kr != 32 && kr != 64 && kr != 128) return false;
+    // groups of up to 16 channels (G* in {1, 2, 4, 8, 16}, Sec. 3.2 and Table 4); K/V tiles other
+    // than 64 rows are built for 16, 32 and 64 groups
+    const int kr = pb.n_groups;
     if (kr > pb.d || pb.d % kr != 0 || pb.d / kr > 16) return false;
+    if (kr == pb.d) return true;
+    if (kr != 4 && kr != 8 && kr != 16 && kr != 32 && kr != 64) return false;
+    if (pb.Bc != 64 && kr < 16) return false;
   }
   return true;
 }
@@ -706,10 +31,9 @@ hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, void* o
                             const void* kt, const Problem& pb, int distr, hipStream_t stream) {
   if (!attn_bf16_supported(pb, distr)) return hipErrorInvalidValue;
   if (distr && !kt) return hipErrorInvalidValue;
-  if (pb.d == 64 && pb.Br == 64) return dispatch_kred<64, 64>(q, k, v, o, perm, kt, pb, distr, stream);
-  if (pb.d == 64 && pb.Br == 128) return dispatch_kred<64, 128>(q, k, v, o, perm, kt, pb, distr, stream);
-  if (pb.d == 128 && pb.Br == 64) return dispatch_kred<128, 64>(q, k, v, o, perm, kt, pb, distr, stream);
-  return dispatch_kred<128, 128>(q, k, v, o, perm, kt, pb, distr, stream);
+  if (pb.Bc == 32) return launch_attn_bf16_bc32(q, k, v, o, perm, kt, pb, distr, stream);
+  if (pb.Bc == 128) return launch_attn_bf16_bc128(q, k, v, o, perm, kt, pb, distr, stream);
+  return launch_attn_bf16_bc64(q, k, v, o, perm, kt, pb, distr, stream);
 }
 
 }  // namespace da

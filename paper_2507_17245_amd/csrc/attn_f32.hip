@@ -176,6 +176,8 @@ hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o,
   else if (pb.d == 64 && pb.Br == 128) DA_F32_LAUNCH(64, 128);
   else if (pb.d == 128 && pb.Br == 64) DA_F32_LAUNCH(128, 64);
   else if (pb.d == 128 && pb.Br == 128) DA_F32_LAUNCH(128, 128);
+  else if (pb.d == 64 && pb.Br == 256) DA_F32_LAUNCH(64, 256);
+  else if (pb.d == 128 && pb.Br == 256) DA_F32_LAUNCH(128, 256);
   else return hipErrorInvalidValue;
 #undef DA_F32_LAUNCH
   return hipGetLastError();

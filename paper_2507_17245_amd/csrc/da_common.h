@@ -16,7 +16,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
-constexpr int kBc = 64;          // key/value rows per tile (the paper's m)
+constexpr int kBc = 64;          // key/value rows per tile of the key pre-pass and the default of the attention kernels
+constexpr int kKtPad = 128;      // K^T rows are padded to a multiple of the largest key tile
 constexpr int kMaxPlanes = 32;   // sign bits per hash
 
 // Projection matrix entry (plane p, row r) of the LSH stage (Sec. 3.2: a fixed random matrix).
@@ -55,7 +56,7 @@ struct Problem {
 // Launchers (defined next to their kernels). All return hipError_t of the launch.
 hipError_t launch_lsh_group(const void* q, int dtype, const Problem& pb, uint8_t* perm_out,
                             uint32_t* hash_out, hipStream_t stream);
-// K [B][Hkv][Nk][d] bf16 -> K^T [B][Hkv][d][Npad] half (Npad = Nk rounded up to kBc), for the distr path.
+// K [B][Hkv][Nk][d] bf16 -> K^T [B][Hkv][d][Npad] half (Npad = Nk rounded up to kKtPad), for the distr path.
 hipError_t launch_kt_prepass(const void* k, void* kt, const Problem& pb, hipStream_t stream);
 // distr != 0: S^ = Q_r K_f^T with the per-block permutation table `perm` [B][H][Tq][d] and the
 // transposed keys `kt` written by launch_kt_prepass (k itself is then unused).

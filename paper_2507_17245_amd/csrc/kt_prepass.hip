@@ -1,6 +1,6 @@
 // Key pre-pass of the DistrAttention path: K [B][Hkv][Nk][d] (bf16, d fastest) is rewritten once
-// per forward as K^T [B][Hkv][d][Npad] in half precision (keys fastest, Npad = N rounded up to
-// the 64-key tile, tail zero-filled).
+// per forward as K^T [B][Hkv][d][Npad] in half precision (keys fastest, Npad = Nk rounded up to
+// the largest key tile, 128, tail zero-filled).
 //
 // Why: the fusion step of Sec. 3.2 sums, for every (Q block, K tile) pair, the key channels of a
 // group chosen by that Q block's permutation. With keys fastest a channel is one contiguous
@@ -57,8 +57,8 @@ __global__ __launch_bounds__(kKtThreads) void kt_prepass_kernel(const bf16* __re
 }
 
 hipError_t launch_kt_prepass(const void* k, void* kt, const Problem& pb, hipStream_t stream) {
-  const int Tk = (pb.Nk + kBc - 1) / kBc;
-  const int Npad = Tk * kBc;
+  const int Npad = (pb.Nk + kKtPad - 1) / kKtPad * kKtPad;
+  const int Tk = Npad / kBc;   // tiles past the last key are written as zeros
   const long long units = (long long)pb.B * pb.Hkv * Tk;
   const float limit = 65504.0f / (float)(pb.d / pb.n_groups);
   dim3 grid((unsigned)units), block(kKtThreads);

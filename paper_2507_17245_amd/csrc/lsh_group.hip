@@ -15,6 +15,7 @@
 namespace da {
 
 constexpr int kLshThreads = 256;
+constexpr int kMaxLshRows = 256;   // largest block the stage hashes (Q blocks up to 256 rows, K blocks up to 128)
 
 template <typename T>
 __device__ inline float to_float(T x);
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(kLshThreads) void lsh_group_kernel(
     int N, int Br, int Tq, int n_planes, int gray_mode, uint64_t seed) {
   constexpr int NPG = kLshThreads / D;        // threads per channel, each takes planes p = j*NPG + pg
   constexpr int PPT = kMaxPlanes / NPG;       // plane slots per thread
-  __shared__ float R_lds[128 * kMaxPlanes];   // [row][pg][j], zero where the plane does not exist
+  __shared__ float R_lds[kMaxLshRows * kMaxPlanes];   // [row][pg][j], zero where the plane does not exist
   __shared__ uint32_t code_lds[D];
   __shared__ uint32_t hash_lds[D];
   __shared__ uint8_t perm_lds[D];
@@ -105,6 +106,7 @@ __global__ __launch_bounds__(kLshThreads) void lsh_group_kernel(
 
 hipError_t launch_lsh_group(const void* q, int dtype, const Problem& pb, uint8_t* perm_out,
                             uint32_t* hash_out, hipStream_t stream) {
+  if (pb.Br < 1 || pb.Br > kMaxLshRows) return hipErrorInvalidValue;
   const int Tq = (pb.N + pb.Br - 1) / pb.Br;
   const long long units = (long long)pb.B * pb.H * Tq;
   dim3 grid((unsigned)units), block(kLshThreads);

@@ -169,7 +169,7 @@ def test_key_prepass_is_an_exact_transpose_and_kt_in_is_honoured():
     kt = torch.zeros(da.distr_attn_kt_bytes(p), dtype=torch.uint8, device="cuda")
     da.distr_attn_key_prepass(tk, kt, p)
     torch.cuda.synchronize()
-    npad = (cfg.N + 63) // 64 * 64
+    npad = (cfg.N + 127) // 128 * 128
     got = kt[:cfg.B * cfg.Hkv * cfg.d * npad * 2].view(torch.float16).view(cfg.B, cfg.Hkv, cfg.d, npad).float().cpu().numpy()
     assert np.array_equal(got[..., :cfg.N], np.swapaxes(k, 2, 3))      # bf16 -> half is exact here
     assert not got[..., cfg.N:].any()                                  # zero-filled tail

@@ -69,7 +69,13 @@ FAKE_O = ctypes.c_void_p(0x2000)
     (dict(softmax_scale=-1.0), da.DA_ERR_INVALID_ARG),
     (dict(d=96, n_groups=48), da.DA_ERR_UNSUPPORTED),
     (dict(Br=32), da.DA_ERR_UNSUPPORTED),
-    (dict(Bc=128), da.DA_ERR_UNSUPPORTED),
+    (dict(Bc=96), da.DA_ERR_UNSUPPORTED),
+    (dict(Br=512), da.DA_ERR_UNSUPPORTED),
+    (dict(Bc=32, n_groups=8), da.DA_ERR_UNSUPPORTED),     # tiles other than 64 rows: 16, 32, 64 groups or d
+    (dict(side=1), da.DA_ERR_UNSUPPORTED),                # the mirrored form is float only
+    (dict(side=2), da.DA_ERR_INVALID_ARG),
+    (dict(Nk=50, causal=1), da.DA_ERR_INVALID_ARG),       # causal with fewer keys than queries
+    (dict(Nk=-1), da.DA_ERR_INVALID_ARG),
     (dict(n_planes=33), da.DA_ERR_UNSUPPORTED),
     (dict(n_groups=2), da.DA_ERR_UNSUPPORTED),            # groups of 32 channels: more than the bf16 kernels take
     (dict(d=128, n_groups=4), da.DA_ERR_UNSUPPORTED),
