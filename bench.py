@@ -20,6 +20,34 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak (published)
+
+
+# Registers per lane of the built attention kernels (exact kernel, from the compiler's resource
+# report), by (d, Bc); they do not depend on Br (a wave always owns 32 query rows).
+KERNEL_VGPRS = {(64, 32): 115, (64, 64): 161, (64, 128): 256, (128, 32): 167, (128, 64): 231, (128, 128): 402}
+
+
+def block_size_rule(d):
+    """The (Br, Bc) = (l, m) that the selection rule of Sec. 3.3 picks with this chip's and this
+    kernel's constants. Eq. 4: l and m are multiples of the matrix unit's tile (32 rows of a
+    32x32x16 MFMA). Eq. 5: the waves resident on a compute unit must be at least twice its matrix
+    units (4, one per SIMD); residency is bounded by the LDS -- 160 KB against 2 * 2 * m * d * w
+    bytes per workgroup (K and V tiles, two buffers each; Q lives in registers, so the paper's l*d
+    term is absent), w = 2 -- and, which the paper's model leaves out, by the register file: 512
+    registers per lane and SIMD against the kernel's count. A workgroup has l / 32 waves. Among the
+    sizes that satisfy both, the largest l, then the largest m."""
+    lds, pipes, w = 160 * 1024, 4, 2
+    best = None
+    for l in (64, 128, 256):
+        for m in (32, 64, 128):
+            waves_per_wg = l // 32
+            wgs_by_lds = lds // (2 * 2 * m * d * w)
+            wgs_by_regs = pipes * (512 // KERNEL_VGPRS[(d, m)]) // waves_per_wg
+            resident = waves_per_wg * min(wgs_by_lds, wgs_by_regs)
+            if resident >= 2 * pipes and (best is None or (l, m) > best):
+                best = (l, m)
+    return best
 
 
 def log(*a):
@@ -81,6 +109,17 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / reps
 
+    def ev_each(fn, reps):
+        """(median, min) in ms over `reps` launches timed one by one with HIP events."""
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in evs:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in evs)
+        return ts[len(ts) // 2], ts[0]
+
     def measure(cfg, n_groups, steps, warmup, tensors):
         q, k, v = tensors
         o = torch.empty_like(q)
@@ -103,6 +142,7 @@ def main():
             step()
         torch.cuda.synchronize()
         ms_step = (time.perf_counter() - t0) * 1e3 / steps
+        ms_step_median, ms_step_min = ev_each(step, steps)
         # the three kernels of the step, one by one
         da.distr_attn_lsh_group(q, p_lsh)
         ms_lsh = ev_time(lambda: da.distr_attn_lsh_group(q, p_lsh), steps)
@@ -121,25 +161,67 @@ def main():
         for _ in range(warmup):
             da.distr_attn_exact_fwd_ex(q, k, v, o_ex, p_ex)
         ms_exact = ev_time(lambda: da.distr_attn_exact_fwd_ex(q, k, v, o_ex, p_ex), steps)
+        ms_exact_median, ms_exact_min = ev_each(lambda: da.distr_attn_exact_fwd_ex(q, k, v, o_ex, p_ex), steps)
         diff = (o.float() - o_ex.float()).abs()
         flops = cfg.exact_flops()
         pairs = cfg.B * cfg.H * visible_pairs(cfg.N, cfg.causal)
+        alg_flops = 2.0 * pairs * (n_groups + cfg.d)
+        esz = 2 if cfg.dtype == "bf16" else 4
+        # compulsory HBM bytes of one forward: Q and O once per query head, K and V once per kv head
+        # (the distr path reads K twice more: the pre-pass reads K and writes K^T, the kernel reads K^T)
+        hbm_bytes = esz * cfg.d * cfg.N * cfg.B * (2 * cfg.H + 2 * cfg.Hkv)
         res = {
             "workload": cfg.name, "B": cfg.B, "H": cfg.H, "Hkv": cfg.Hkv, "N": cfg.N, "d": cfg.d,
             "dtype": cfg.dtype, "causal": cfg.causal, "Br": cfg.Br, "Bc": cfg.Bc, "n_groups": n_groups,
-            "ms_per_forward": ms_step, "eff_tflops": flops / ms_step / 1e9,
-            "pct_bf16_peak": 100.0 * flops / ms_step / 1e9 / PEAK_BF16_TFLOPS,
+            "ms_per_forward": ms_step, "ms_per_forward_median": ms_step_median, "ms_per_forward_min": ms_step_min,
+            "eff_tflops": flops / ms_step / 1e9,
             "ms_lsh_kernel": ms_lsh, "lsh_in_attention_kernel": lsh_in_kernel,
             "ms_key_prepass_kernel": ms_prepass, "ms_attn_kernel": ms_attn,
-            "ms_exact_kernel": ms_exact, "exact_eff_tflops": flops / ms_exact / 1e9,
+            "ms_exact_kernel": ms_exact, "ms_exact_kernel_median": ms_exact_median, "ms_exact_kernel_min": ms_exact_min,
+            "exact_eff_tflops": flops / ms_exact / 1e9,
             "speedup_vs_exact_kernel": ms_exact / ms_step,
-            "attn_kernel_algorithmic_flops": 2.0 * pairs * (n_groups + cfg.d),
+            "attn_kernel_algorithmic_flops": alg_flops,
             "exact_kernel_algorithmic_flops": 4.0 * pairs * cfg.d,
             "approx_err_vs_exact_kernel": {"max_abs": float(diff.max()), "mean_abs": float(diff.mean())},
         }
         if cfg.causal:
             res["executed_eff_tflops"] = res["eff_tflops"] * pairs / (cfg.B * cfg.H * cfg.N * cfg.N)
+        if cfg.dtype == "bf16":
+            # executed work against the peaks: the attention kernel's algorithmic FLOPs against the dense
+            # bf16 matrix peak, and the forward's compulsory bytes against the HBM peak (the small
+            # configurations are bound by the latter and by launch latency)
+            res["roofline"] = {
+                "mfma_frac": alg_flops / (ms_attn * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                "exact_kernel_mfma_frac": 4.0 * pairs * cfg.d / (ms_exact * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                "hbm_gbs": hbm_bytes / (ms_step * 1e-3) / 1e9,
+                "hbm_frac": hbm_bytes / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                "compulsory_hbm_bytes": hbm_bytes,
+            }
         return res
+
+    def block_size_table(cfg, n_groups, tensors, reps):
+        """Sec. 3.3 / Table 2 on this chip: every (Br, Bc) the kernels are built for, exact and
+        DistrAttention forward (ms), beside the pick of the selection rule redone for MI355X."""
+        q, k, v = tensors
+        o = torch.empty_like(q)
+        rows = []
+        for Br in (64, 128, 256):
+            for Bc in (32, 64, 128):
+                common = dict(Br=Br, Bc=Bc, causal=cfg.causal, n_planes=cfg.n_planes, lsh_seed=cfg.lsh_seed)
+                p_d = da.make_params(q, k, v, n_groups=n_groups, **common)
+                p_e = da.make_params(q, k, v, **common)
+                for _ in range(3):
+                    da.distr_attn_fwd_ex(q, k, v, o, p_d)
+                    da.distr_attn_exact_fwd_ex(q, k, v, o, p_e)
+                ms_d = ev_time(lambda: da.distr_attn_fwd_ex(q, k, v, o, p_d), reps)
+                ms_e = ev_time(lambda: da.distr_attn_exact_fwd_ex(q, k, v, o, p_e), reps)
+                rows.append({"Br": Br, "Bc": Bc, "ms_distr_forward": ms_d, "ms_exact_kernel": ms_e})
+        best_d = min(rows, key=lambda r: r["ms_distr_forward"])
+        best_e = min(rows, key=lambda r: r["ms_exact_kernel"])
+        rule = block_size_rule(cfg.d)
+        return {"workload": cfg.name, "d": cfg.d, "N": cfg.N, "n_groups": n_groups, "table": rows,
+                "best_distr": [best_d["Br"], best_d["Bc"]], "best_exact": [best_e["Br"], best_e["Bc"]],
+                "rule_pick": list(rule)}
 
     results = {}
     head_cfg = W.CONFIGS[args.workload]
@@ -158,9 +240,15 @@ def main():
         for ng in groups:
             r = measure(cfg, ng, steps, args.warmup, tensors)
             results[f"{name}_k{ng}"] = r
-            log(f"[bench] {name} k={ng}: {r['ms_per_forward']:.3f} ms/fwd, {r['eff_tflops']:.1f} eff TFLOP/s "
-                f"({r['pct_bf16_peak']:.1f}% of bf16 peak), exact kernel {r['ms_exact_kernel']:.3f} ms, "
-                f"speed-up {r['speedup_vs_exact_kernel']:.2f}")
+            log(f"[bench] {name} k={ng}: {r['ms_per_forward']:.3f} ms/fwd, {r['eff_tflops']:.1f} eff TFLOP/s, "
+                f"exact kernel {r['ms_exact_kernel']:.3f} ms, speed-up {r['speedup_vs_exact_kernel']:.2f}")
+        if not args.only and name in ("llama", "mid"):
+            # the block-size experiment of Sec. 3.3 (Table 2) on the d = 64 and the d = 128 shape
+            ng = cfg.n_groups
+            results[f"block_sizes_d{cfg.d}"] = block_size_table(cfg, ng, tensors, max(3, args.steps // 4))
+            t = results[f"block_sizes_d{cfg.d}"]
+            log(f"[bench] block sizes d={cfg.d}: best distr {t['best_distr']}, best exact {t['best_exact']}, "
+                f"rule {t['rule_pick']}")
         if name == args.workload:
             head_inputs = host
         del tensors
@@ -218,18 +306,20 @@ def main():
         "metric": "effective attention TFLOP/s (4*B*H*N^2*d / time of one DistrAttention forward)",
         "value": head["eff_tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": head["ms_per_forward"], "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 (reduced product Q_r K_f^T in f16), fp32 accumulate", "data": "synthetic",
         "config": {"workload": f"{head_cfg.name}: B={head_cfg.B} H={head_cfg.H} N={head_cfg.N} d={head_cfg.d} "
                                f"bf16 {'causal' if head_cfg.causal else 'non-causal'} Br={head_cfg.Br} "
                                f"Bc={head_cfg.Bc} n_groups={head_cfg.n_groups}",
                    "recipe": head_cfg.recipe},
-        "pct_bf16_peak": head["pct_bf16_peak"],
+        "ms_per_step_median": head["ms_per_forward_median"], "ms_per_step_min": head["ms_per_forward_min"],
         "speedup_vs_exact_kernel": head["speedup_vs_exact_kernel"],
         "executed_eff_tflops": head.get("executed_eff_tflops", head["eff_tflops"]),
         "value_note": "value counts the exact-attention FLOPs of the full N x N problem (4*B*H*N^2*d), the metric's "
-                      "convention for the approximate and the exact kernel alike; under the causal mask half of them "
-                      "are executed (executed_eff_tflops), and the approximation executes fewer still (roofline.achieved "
-                      "counts those)",
+                      "convention for the approximate and the exact kernel alike, so it is not a utilisation and may "
+                      "exceed the chip's peak; under the causal mask half of those FLOPs are executed "
+                      "(executed_eff_tflops), and the approximation executes fewer still: roofline.achieved / "
+                      "roofline.frac count the executed ones",
         "paper_context": "paper reports up to 37% faster than FlashAttention-2 on RTX 4090 / L40 (Sec. 4.5)",
         "roofline": roofline, "cpu_baseline": cpu, "configs": results,
     }
