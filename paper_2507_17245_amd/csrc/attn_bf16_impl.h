@@ -217,6 +217,32 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
   const int q_abs = qw0 + lq;                  // this lane's query row
   const int q_ld = min(q_abs, N - 1);          // ragged block: load a valid row, never store it
 
+  // distr at d = 64: the Q block first lands in LDS by direct loads, all in flight at once
+  // (16-byte chunks, rows past N zero-filled by the range check); the LSH stage and the sampling
+  // then read its columns from there. Walking the columns in global memory instead costs the
+  // workgroup one memory round trip per 16 rows and another for the sampled columns, which at
+  // d = 64, where a block only has a few short tiles of work, is a large part of its lifetime.
+  // (At d = 128 the stage is a percent of the block's time and the 32 KB are not spent.)
+  constexpr bool QSTAGE = DISTR && D == 64;
+  __shared__ __attribute__((aligned(1024))) char q_stage[QSTAGE ? BR * C::ROWB : 16];
+  // (a generic lambda, like the other direct loads below: the builtins exist for the device only,
+  // and a template is not checked against the host's builtin set)
+  auto stage_q_block = [&](auto n_c, char* dst) {
+    typedef __attribute__((address_space(3))) void lds_void_q;
+    const __amdgpu_buffer_rsrc_t q_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)qh, 0, (unsigned)N * D * 2, 0x00020000);
+#pragma unroll
+    for (int j = 0; j < decltype(n_c)::value; ++j) {
+      const int blk = j * C::NW + wave;
+      const int slot = blk * 64 + lane;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(q_rsrc, (lds_void_q*)(dst + blk * 1024), 16,
+                                               (slot / (D / 8)) * (D * 2) + (slot % (D / 8)) * 16, r0 * (D * 2), 0, 0);
+    }
+  };
+  if constexpr (QSTAGE) {
+    constexpr int QBLK = BR * C::ROWB / 1024;      // 1 KB blocks of the Q block
+    static_assert(QBLK % C::NW == 0, "whole blocks per wave");
+    stage_q_block(std::integral_constant<int, QBLK / C::NW>(), q_stage);
+  }
   if constexpr (DISTR) {
     if (perm != nullptr) {
       const size_t pbase = ((size_t)bh * Tq + t) * D;
@@ -242,15 +268,16 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
       for (int i = tid; i < BR * 16; i += C::T)
         R_lds[i] = (i & 15) < n_planes ? hyperplane_entry(lsh_seed, (uint32_t)(i & 15), (uint32_t)(i >> 4)) : 0.0f;
       if (tid < D) code_lds[tid] = 0;
+      if constexpr (QSTAGE) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of the Q block has landed
       __syncthreads();
       const int c = tid % D, pg = tid / D;
       const int rows = min(BR, N - r0);
-      const bf16* qcol = qh + (size_t)r0 * D + c;
+      const bf16* qcol = QSTAGE ? (const bf16*)q_stage + c : qh + (size_t)r0 * D + c;
       float acc[PPT];
 #pragma unroll
       for (int j = 0; j < PPT; ++j) acc[j] = 0.0f;
-      // 16 column loads in flight per thread: with two workgroups per CU nothing else hides
-      // their latency here (the stand-alone kernel, at 8 workgroups per CU, does with 4).
+      // (not staged: 16 column loads in flight per thread, because with two workgroups per CU
+      // nothing else hides their latency here)
 #pragma unroll 16
       for (int r = 0; r < rows; ++r) {
         const float x = (float)qcol[(size_t)r * D];
@@ -278,6 +305,7 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
         perm_lds[rank] = (uint8_t)tid;
       }
     }
+    if constexpr (QSTAGE) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if constexpr (NG < KRED) {
       // Rows NG..KRED-1 of K_f^T pad the contraction: zeroed once (after the LSH stage, which may
@@ -303,7 +331,8 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
   // factor is applied to the float scores, one fused multiply-add per score.
   kx8 qop[C::KSTEPS];
   if constexpr (DISTR) {
-    const bf16* qrow = qh + (size_t)q_ld * D;
+    // (staged block: a row past N reads as zeros and is never stored)
+    const bf16* qrow = QSTAGE ? (const bf16*)q_stage + (wave * 32 + lq) * D : qh + (size_t)q_ld * D;
 #pragma unroll
     for (int s = 0; s < C::KSTEPS; ++s) {
 #pragma unroll
