@@ -96,13 +96,15 @@ __device__ inline int v_swizzle(int row) {
   static_assert(ROW_BYTES == 256 || ROW_BYTES == 128, "row length");
   return ROW_BYTES == 256 ? ((row & 3) << 1) : (row & 2);
 }
-// The fused tile K_f^T (128-byte rows) keeps a swizzle that leaves a two-way conflict on its
-// transposing reads: those reads are limited by the return path, not by the banks (same
-// throughput in a micro-benchmark), and the kernels built with the conflict-free form (row & 2)
-// were measured within 1 % at d = 128 and 4 % slower at d = 64.
-// (Rows of BC * 2 bytes hold BC / 16 segments; the swizzle stays inside the row.)
+// The fused tile K_f^T (rows of 2*BC bytes, one per group) is read with the same transposing
+// accesses and takes the same swizzle as a V tile with rows of that length; rows of 64 bytes
+// (BC = 32) hold two segments, exchanged on every second pair of rows.
 template <int BC>
-__device__ inline int kf_swizzle(int row) { return (row >> 1) & (BC >= 64 ? 3 : 1); }
+__device__ inline int kf_swizzle(int row) {
+  if constexpr (BC == 64) return v_swizzle<128>(row);
+  else if constexpr (BC == 128) return v_swizzle<256>(row);
+  else return (row >> 1) & 1;
+}
 
 // KRED: contraction length of the score product (a multiple of the MFMA step, 16). NG: number of
 // channel groups; smaller than KRED only for n_groups 4 and 8, whose operands are zero-padded to 16.
