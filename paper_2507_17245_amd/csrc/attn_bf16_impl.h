@@ -227,6 +227,15 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
   // (At d = 128 the stage is a percent of the block's time and the 32 KB are not spent.)
   constexpr bool QSTAGE = DISTR && D == 64;
   __shared__ __attribute__((aligned(1024))) char q_stage[QSTAGE ? BR * C::ROWB : 16];
+  // The 16-byte chunks of a staged row are exchanged by the row index (chunk ^ (row & 7)): the
+  // sampling reads one column of 32 different rows at once, which would otherwise all fall into
+  // one bank; reading a whole row (the LSH stage: lanes = channels) is conflict-free either way.
+  // (Blocks of 64 rows measured 5 % faster without the exchange -- their sampling is a small part
+  // of a prologue that the LSH stage dominates -- so it is applied from 128 rows on.)
+  constexpr int QSWZ = BR >= 128 ? 7 : 0;
+  auto q_staged = [&](int row, int ch) -> bf16 {
+    return *(const bf16*)(q_stage + row * C::ROWB + (((ch >> 3) ^ (row & QSWZ)) << 4) + (ch & 7) * 2);
+  };
   // (a generic lambda, like the other direct loads below: the builtins exist for the device only,
   // and a template is not checked against the host's builtin set)
   auto stage_q_block = [&](auto n_c, char* dst) {
@@ -237,7 +246,8 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
       const int blk = j * C::NW + wave;
       const int slot = blk * 64 + lane;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(q_rsrc, (lds_void_q*)(dst + blk * 1024), 16,
-                                               (slot / (D / 8)) * (D * 2) + (slot % (D / 8)) * 16, r0 * (D * 2), 0, 0);
+                                               (slot / (D / 8)) * (D * 2) + ((slot % (D / 8)) ^ ((slot / (D / 8)) & (BR >= 128 ? 7 : 0))) * 16,
+                                               r0 * (D * 2), 0, 0);
     }
   };
   if constexpr (QSTAGE) {
@@ -274,17 +284,37 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
       __syncthreads();
       const int c = tid % D, pg = tid / D;
       const int rows = min(BR, N - r0);
-      const bf16* qcol = QSTAGE ? (const bf16*)q_stage + c : qh + (size_t)r0 * D + c;
+      const bf16* qcol = qh + (size_t)r0 * D + c;
       float acc[PPT];
 #pragma unroll
       for (int j = 0; j < PPT; ++j) acc[j] = 0.0f;
       // (not staged: 16 column loads in flight per thread, because with two workgroups per CU
       // nothing else hides their latency here)
-#pragma unroll 16
-      for (int r = 0; r < rows; ++r) {
-        const float x = (float)qcol[(size_t)r * D];
+      if constexpr (QSTAGE) {
+        // Staged block: rows past N are zeros, and fma(0, R, acc) leaves acc as it is bit for bit,
+        // so all BR rows are walked (constant trip count); eight rows per step make the row's
+        // chunk exchange a constant of the unrolled step.
+        const char* col = q_stage + (c & 7) * 2;
+        int chunk_off[8];
 #pragma unroll
-        for (int j = 0; j < PPT; ++j) acc[j] = __builtin_fmaf(x, R_lds[r * 16 + pg * PPT + j], acc[j]);
+        for (int j8 = 0; j8 < 8; ++j8) chunk_off[j8] = j8 * C::ROWB + (((c >> 3) ^ (j8 & QSWZ)) << 4);
+#pragma unroll 2
+        for (int r8 = 0; r8 < BR; r8 += 8) {
+#pragma unroll
+          for (int j8 = 0; j8 < 8; ++j8) {
+            const float x = (float)*(const bf16*)(col + r8 * C::ROWB + chunk_off[j8]);
+#pragma unroll
+            for (int j = 0; j < PPT; ++j)
+              acc[j] = __builtin_fmaf(x, R_lds[(r8 + j8) * 16 + pg * PPT + j], acc[j]);
+          }
+        }
+      } else {
+#pragma unroll 16
+        for (int r = 0; r < rows; ++r) {
+          const float x = (float)qcol[(size_t)r * D];
+#pragma unroll
+          for (int j = 0; j < PPT; ++j) acc[j] = __builtin_fmaf(x, R_lds[r * 16 + pg * PPT + j], acc[j]);
+        }
       }
       uint32_t bits = 0;
 #pragma unroll
@@ -334,13 +364,14 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
   kx8 qop[C::KSTEPS];
   if constexpr (DISTR) {
     // (staged block: a row past N reads as zeros and is never stored)
-    const bf16* qrow = QSTAGE ? (const bf16*)q_stage + (wave * 32 + lq) * D : qh + (size_t)q_ld * D;
+    const bf16* qrow = qh + (size_t)q_ld * D;
 #pragma unroll
     for (int s = 0; s < C::KSTEPS; ++s) {
 #pragma unroll
       for (int j = 0; j < 8; ++j)
         if (NG == KRED || 16 * s + 8 * hh + j < NG)
-          qop[s][j] = to_half_sat((float)qrow[perm_lds[(16 * s + 8 * hh + j) * C::G]] * scale_log2e);
+          qop[s][j] = to_half_sat((QSTAGE ? (float)q_staged(wave * 32 + lq, perm_lds[(16 * s + 8 * hh + j) * C::G])
+                                          : (float)qrow[perm_lds[(16 * s + 8 * hh + j) * C::G]]) * scale_log2e);
         else
           qop[s][j] = (f16)0.0f;   // padding of the contraction: no group there
     }
