@@ -261,7 +261,7 @@ def main():
     # by a plain copy of known size); the committed summary carries the figure for its workload.
     traffic = None
     try:
-        with open(os.path.join(ROOT, "profiles", "attn_bf16_long_hbm_traffic.md")) as f:
+        with open(os.path.join(ROOT, "profiles", f"attn_bf16_{args.workload}_hbm_traffic.md")) as f:
             for line in f:
                 if line.startswith("bench-traffic:"):
                     rec = json.loads(line.split(":", 1)[1])
