@@ -42,10 +42,11 @@ typedef enum { DA_BF16 = 0, DA_F32 = 1 } da_dtype;
 /*
  * Full parameter block (host memory).
  *
- * Supported by the kernels: d in {64, 128}; Br in {64, 128}; Bc = 64; for bf16 n_groups in
- * {4, 8, 16, 32, 64, 128} with G* = d / n_groups <= 16 (4 and 8 zero-pad the contraction to one MFMA
- * step of 16), for float any divisor of d; 1 <= n_planes <= 32;
- * N >= 1 arbitrary (ragged last blocks are masked), N * d * 4 < 2^31; at most 2^31 - 1 query blocks.
+ * Supported by the kernels: d in {64, 128}; Br in {64, 128, 256}; Bc in {32, 64, 128}; for bf16
+ * n_groups in {4, 8, 16, 32, 64, 128} with G* = d / n_groups <= 16 (4 and 8 zero-pad the contraction
+ * to one MFMA step of 16, and need Bc = 64), for float any divisor of d; 1 <= n_planes <= 32;
+ * N, Nk >= 1 arbitrary (ragged last blocks are masked), N * d * 4 and Nk * d * 4 < 2^31; at most
+ * 2^31 - 1 query blocks.
  * bf16 DistrAttention path: the reduced product S^ = Q_r K_f^T runs in half precision on
  * Q_r * softmax_scale * log2(e) and on K. Full precision needs magnitudes inside half's normal
  * range: |q| * softmax_scale * log2(e) beyond 65504 and |k| beyond 65504 / G* are clamped; below
