@@ -177,3 +177,46 @@ def scores(q, k, p, b=0, h=0, R=None, perm=None, want_exact=True, want_hat=True)
                                ctypes.byref(p), Rp, _ptr(perm, ctypes.c_uint8), b, h),
            "oracle_scores")
     return s_hat, s
+
+
+def lse(q, k, p, distr=True, R=None, perm=None):
+    """-> float64 [B,H,N]: log-sum-exp of every row's visible scores (S^ if distr else S)."""
+    q, qp = _f32(q)
+    k, kp = _f32(k)
+    Rp = None
+    if R is not None:
+        R, Rp = _f32(R)
+    if perm is not None:
+        perm = np.ascontiguousarray(perm, dtype=np.uint8)
+    out = np.zeros((p.B, p.H, p.N), dtype=np.float64)
+    _check(lib().oracle_lse(qp, kp, _ptr(out, ctypes.c_double), ctypes.byref(p), Rp,
+                            _ptr(perm, ctypes.c_uint8), int(bool(distr))), "oracle_lse")
+    return out
+
+
+def _bwd(name, q, k, v, dout, p, extra):
+    q, qp = _f32(q)
+    k, kp = _f32(k)
+    v, vp = _f32(v)
+    dout, dop = _f32(dout)
+    dq = np.zeros((p.B, p.H, p.N, p.d), dtype=np.float64)
+    dk = np.zeros((p.B, p.Hkv, n_keys(p), p.d), dtype=np.float64)
+    dv = np.zeros_like(dk)
+    _check(getattr(lib(), name)(qp, kp, vp, dop, _ptr(dq, ctypes.c_double), _ptr(dk, ctypes.c_double),
+                                _ptr(dv, ctypes.c_double), ctypes.byref(p), *extra), name)
+    return dq, dk, dv
+
+
+def exact_bwd(q, k, v, dout, p):
+    """-> (dq, dk, dv) float64: gradient of sum(dout * exact_fwd) (Sec. 2.1)."""
+    return _bwd("oracle_exact_bwd", q, k, v, dout, p, ())
+
+
+def distr_bwd(q, k, v, dout, p, R=None, perm=None):
+    """-> (dq, dk, dv) float64: gradient of sum(dout * distr_fwd) with the grouping held fixed."""
+    Rp = None
+    if R is not None:
+        R, Rp = _f32(R)
+    if perm is not None:
+        perm = np.ascontiguousarray(perm, dtype=np.uint8)
+    return _bwd("oracle_distr_bwd", q, k, v, dout, p, (Rp, _ptr(perm, ctypes.c_uint8)))

@@ -4,7 +4,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "distr_attn_oracle.c")
+SRCS = [os.path.join(HERE, "distr_attn_oracle.c"), os.path.join(HERE, "distr_attn_oracle_bwd.c")]
 OUT = os.path.join(HERE, "libdistr_attn_oracle.so")
 
 
@@ -12,7 +12,7 @@ def build(verbose: bool = False) -> str:
     # -ffp-contract=off: no multiply-add is fused unless the source says fmaf;
     # -mfma: fmaf is the hardware instruction (correctly rounded either way).
     cmd = ["gcc", "-std=c11", "-O2", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-           "-mfma", "-Wall", "-Wextra", "-o", OUT, SRC, "-lm"]
+           "-mfma", "-Wall", "-Wextra", "-o", OUT, *SRCS, "-lm"]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -88,6 +88,23 @@ int oracle_distr_fwd_tiles(const float *q, const float *k, const float *v, doubl
 int oracle_scores(const float *q, const float *k, double *s_hat, double *s,
                   const oracle_params *p, const float *R, const uint8_t *perm, int b, int h);
 
+/* Row statistics of the forward: lse[b][h][i] = log of the sum over the visible keys of
+ * exp(score), scores = S^ (distr != 0; R and perm as for oracle_distr_fwd) or S (distr == 0).
+ * lse is [B][H][N]. Side 0 only. */
+int oracle_lse(const float *q, const float *k, double *lse, const oracle_params *p, const float *R,
+               const uint8_t *perm, int distr);
+
+/* Backward pass (distr_attn_oracle_bwd.c): gradients of sum(dout * O) with respect to q, k, v.
+ * The paper gives no gradient (Sec. 4.3-4.4 only train through the method); this is the
+ * derivative of the forward with every Q block's grouping held fixed: only the sampled Q columns
+ * of a block receive a gradient, every member of a K group receives its group's. dout is
+ * [B][H][N][d]; dq [B][H][N][d], dk and dv [B][Hkv][Nk][d] are overwritten. Side 0 only. */
+int oracle_exact_bwd(const float *q, const float *k, const float *v, const float *dout, double *dq,
+                     double *dk, double *dv, const oracle_params *p);
+int oracle_distr_bwd(const float *q, const float *k, const float *v, const float *dout, double *dq,
+                     double *dk, double *dv, const oracle_params *p, const float *R,
+                     const uint8_t *perm);
+
 /* Threads the parallel loops will use. */
 int oracle_num_threads(void);
 

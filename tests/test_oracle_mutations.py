@@ -13,6 +13,7 @@ import pytest
 
 import oracle
 import test_oracle as pins
+import test_oracle_bwd as bwd_pins
 
 SRC_DIR = os.path.dirname(os.path.abspath(oracle.__file__))
 
@@ -74,22 +75,30 @@ MUTANTS = [
 ]
 
 
-def _build(source_text, workdir, tag):
+BWD_SRC = os.path.join(SRC_DIR, "distr_attn_oracle_bwd.c")
+
+
+def _build(source_text, workdir, tag, bwd_text=None):
     c_path = os.path.join(workdir, f"oracle_{tag}.c")
     so_path = os.path.join(workdir, f"oracle_{tag}.so")
     with open(c_path, "w") as f:
         f.write(source_text)
+    bwd_path = BWD_SRC
+    if bwd_text is not None:
+        bwd_path = os.path.join(workdir, f"oracle_bwd_{tag}.c")
+        with open(bwd_path, "w") as f:
+            f.write(bwd_text)
     subprocess.run(["gcc", "-std=c11", "-O1", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-mfma",
-                    "-I", SRC_DIR, "-o", so_path, c_path, "-lm"], check=True)
+                    "-I", SRC_DIR, "-o", so_path, c_path, bwd_path, "-lm"], check=True)
     lib = ctypes.CDLL(so_path)
     lib.oracle_gray_hash.restype = ctypes.c_uint32
     lib.oracle_gray_hash.argtypes = [ctypes.c_uint32, ctypes.c_int, ctypes.c_int]
     return lib
 
 
-def _failing_pins():
+def _failing_pins(funcs=None):
     failed = []
-    for i, fn in enumerate(PIN_FUNCS):
+    for i, fn in enumerate(PIN_FUNCS if funcs is None else funcs):
         try:
             fn()
         except (AssertionError, ValueError):
@@ -114,3 +123,48 @@ def test_pins_catch_a_planted_mistake(source, monkeypatch, name, old, new):
     with tempfile.TemporaryDirectory() as tmp:
         monkeypatch.setattr(oracle, "_lib", _build(source.replace(old, new), tmp, "mutant"))
         assert _failing_pins(), f"no pin noticed: {name}"
+
+
+# The backward pass and the row statistics (distr_attn_oracle_bwd.c) against their own pins.
+BWD_PIN_FUNCS = [
+    lambda: [bwd_pins.test_distr_backward_matches_automatic_differentiation(kw) for kw in bwd_pins.CASES],
+    lambda: [bwd_pins.test_exact_backward_matches_library_attention(kw) for kw in
+             (dict(), dict(causal=True), dict(H=6, Hkv=2, N=13, Nk=31, causal=True))],
+    lambda: [bwd_pins.test_backward_is_the_finite_difference_of_the_forward(c) for c in (False, True)],
+    bwd_pins.test_structure_of_the_gradient,
+    lambda: [bwd_pins.test_row_statistics(kw) for kw in (dict(), dict(causal=True, N=20, Nk=29), dict(H=4, Hkv=2, causal=True))],
+]
+
+BWD_MUTANTS = [
+    ("row term D dropped from dS", "const double ds = s[n] * (dp - D);", "const double ds = s[n] * dp;"),
+    ("dV weighted by dS instead of P", "dvh[(size_t)n * d + c] += s[n] * (double)doi[c];", "dvh[(size_t)n * d + c] += s[n] * (dp - D) * (double)doi[c];"),
+    ("dQ lands on the group's last member", "dqh[(size_t)i * d + perm[j * G]] = p->scale * dqr[j];", "dqh[(size_t)i * d + perm[j * G + G - 1]] = p->scale * dqr[j];"),
+    ("dQ spread over every member of the group", "for (int j = 0; j < ng; ++j) dqh[(size_t)i * d + perm[j * G]] = p->scale * dqr[j];",
+     "for (int j = 0; j < ng; ++j) for (int g = 0; g < G; ++g) dqh[(size_t)i * d + perm[j * G + g]] = p->scale * dqr[j];"),
+    ("dK only to the group's first member", "for (int g = 0; g < G; ++g)\n                  dkh[", "for (int g = 0; g < 1; ++g)\n                  dkh["),
+    ("dK without the scale", "+= p->scale * dkf[(size_t)n * ng + j];", "+= dkf[(size_t)n * ng + j];"),
+    ("dK_f taken with the unsampled column", "dkf[(size_t)n * ng + j] += ds * (double)qi[perm[j * G]];", "dkf[(size_t)n * ng + j] += ds * (double)qi[perm[j * G + G - 1]];"),
+    ("gradient forgets the other query heads of a kv head", "for (int h = hk * rep; h < (hk + 1) * rep; ++h) {", "for (int h = hk * rep; h < hk * rep + 1; ++h) {"),
+    ("causal shift dropped in the backward", "const int n_vis = p->causal ? i + shift + 1 : Nk;\n              const float *qi", "const int n_vis = p->causal ? i + 1 : Nk;\n              const float *qi"),
+    ("row statistics without the maximum added back", "lse[(size_t)bh * N + i] = m + log(sum);", "lse[(size_t)bh * N + i] = log(sum);"),
+    ("row statistics of the exact scores for the approximation", "const uint8_t *perm = distr ? table + ((size_t)bh * Tq + i / Br) * d : NULL;", "const uint8_t *perm = NULL;"),
+]
+
+
+@pytest.fixture(scope="module")
+def bwd_source():
+    return open(BWD_SRC).read()
+
+
+def test_untouched_backward_source_passes_its_pins(source, bwd_source, monkeypatch):
+    with tempfile.TemporaryDirectory() as tmp:
+        monkeypatch.setattr(oracle, "_lib", _build(source, tmp, "clean", bwd_source))
+        assert _failing_pins(BWD_PIN_FUNCS) == []
+
+
+@pytest.mark.parametrize("name,old,new", BWD_MUTANTS, ids=[m[0] for m in BWD_MUTANTS])
+def test_backward_pins_catch_a_planted_mistake(source, bwd_source, monkeypatch, name, old, new):
+    assert bwd_source.count(old) == 1, f"mutation site for '{name}' not found (or not unique) in the backward source"
+    with tempfile.TemporaryDirectory() as tmp:
+        monkeypatch.setattr(oracle, "_lib", _build(source, tmp, "mutant", bwd_source.replace(old, new)))
+        assert _failing_pins(BWD_PIN_FUNCS), f"no pin noticed: {name}"
