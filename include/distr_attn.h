@@ -90,6 +90,10 @@ typedef struct {
                            sample K columns, fuse Q columns, one grouping per K block of Bc rows taken
                            from that K block; float only, Bc in {32, 64, 128}; perm_in / perm_out /
                            hash_out are then [B][Hkv][Tk][d]                                        */
+  float *lse_out;       /* optional device [B][H][N] float: natural logarithm of the sum over the visible
+                           keys of exp(score) of every query row -- the row statistics of the softmax
+                           (Sec. 2.2.2), which a backward pass needs; scores are S^ for the
+                           DistrAttention calls and S for the exact ones. side = 0 only              */
 } da_params;
 
 /*
@@ -111,6 +115,28 @@ int distr_attn_exact_fwd(const void *q, const void *k, const void *v, void *o, i
  * distr_attn_lsh_group, no table is written); otherwise the stage is a kernel of its own. */
 int distr_attn_fwd_ex(const void *q, const void *k, const void *v, void *o, const da_params *p);
 int distr_attn_exact_fwd_ex(const void *q, const void *k, const void *v, void *o, const da_params *p);
+
+/*
+ * Backward pass of the two calls above, float path only (dtype = DA_F32, side = 0). The paper
+ * trains through the method (Sec. 4.3, 4.4) without giving a gradient; computed here is the
+ * derivative of the forward with every query block's grouping held fixed (the grouping is a
+ * piecewise-constant function of q): with P = softmax(S^), dP = dout V^T, D_i = sum_c dout_ic o_ic
+ * and dS^ = P o (dP - D),  dv = P^T dout;  dq[:, first channel of group j] = scale (dS^ K_f)[:, j]
+ * and 0 in the block's other columns;  dk[:, c] = scale * sum over query blocks of
+ * (dS^T Q_r)[:, group of c in that block]  (Q_r, K_f: sampled and fused columns, Sec. 3.2, Eq. 2).
+ * The exact call is the case of one channel per group (Sec. 2.1).
+ * q, k, v, p: as given to the forward; o: its output; lse: its lse_out; dout [B][H][N][d]: gradient
+ * of the loss with respect to o. Written: dq [B][H][N][d], dk and dv [B][Hkv][Nk][d] (float, device,
+ * 16-byte aligned, distinct from every input and from each other). The grouping is recomputed
+ * from q (same seed and options give the forward's table) unless p->perm_in brings it; the table
+ * lives in the workspace as in the forward. No atomics: results are the same on every run.
+ * Errors: as the forward; DA_ERR_UNSUPPORTED for bf16 or side = 1.
+ */
+int distr_attn_bwd_ex(const void *q, const void *k, const void *v, const void *o, const void *dout,
+                      const float *lse, void *dq, void *dk, void *dv, const da_params *p);
+int distr_attn_exact_bwd_ex(const void *q, const void *k, const void *v, const void *o,
+                            const void *dout, const float *lse, void *dq, void *dk, void *dv,
+                            const da_params *p);
 
 /*
  * LSH hash-and-group stage alone (Sec. 3.2 "similar columns identification", Fig. 5): writes

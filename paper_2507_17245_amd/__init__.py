@@ -17,6 +17,7 @@ DA_BF16, DA_F32 = 0, 1
 EXPORTS = (
     "distr_attn_fwd", "distr_attn_exact_fwd", "distr_attn_fwd_ex", "distr_attn_exact_fwd_ex",
     "distr_attn_fwd_noalloc", "distr_attn_noalloc_max_bytes",
+    "distr_attn_bwd_ex", "distr_attn_exact_bwd_ex",
     "distr_attn_lsh_group", "distr_attn_key_prepass", "distr_attn_kt_bytes",
     "distr_attn_workspace_bytes", "distr_attn_hyperplanes",
     "distr_attn_set_stream", "distr_attn_release", "distr_attn_last_error", "distr_attn_version",
@@ -33,7 +34,7 @@ class DaParams(ctypes.Structure):
         ("stream", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_size_t), ("perm_out", ctypes.c_void_p),
         ("hash_out", ctypes.c_void_p), ("perm_in", ctypes.c_void_p), ("kt_in", ctypes.c_void_p),
-        ("Nk", ctypes.c_int), ("side", ctypes.c_int),
+        ("Nk", ctypes.c_int), ("side", ctypes.c_int), ("lse_out", ctypes.c_void_p),
     ]
 
 
@@ -59,6 +60,8 @@ def lib():
         L.distr_attn_noalloc_max_bytes.restype = ctypes.c_size_t
         for name in ("distr_attn_fwd_ex", "distr_attn_exact_fwd_ex", "distr_attn_fwd_noalloc"):
             getattr(L, name).argtypes = [vp, vp, vp, vp, ctypes.POINTER(DaParams)]
+        for name in ("distr_attn_bwd_ex", "distr_attn_exact_bwd_ex"):
+            getattr(L, name).argtypes = [vp] * 9 + [ctypes.POINTER(DaParams)]
         L.distr_attn_lsh_group.argtypes = [vp, ctypes.POINTER(DaParams)]
         L.distr_attn_key_prepass.argtypes = [vp, vp, ctypes.POINTER(DaParams)]
         for name in ("distr_attn_workspace_bytes", "distr_attn_kt_bytes"):
@@ -131,9 +134,10 @@ def _check_buffer(t, name, min_bytes):
 
 def make_params(q, k, v, Br, Bc=64, n_groups=None, causal=False, lsh_seed=0, n_planes=0,
                 softmax_scale=0.0, gray_mode=0, workspace=None, perm_out=None, hash_out=None,
-                perm_in=None, kt_in=None, side=0):
+                perm_in=None, kt_in=None, side=0, lse_out=None):
     """side=1: the mirrored form (sample K, fuse Q, one grouping per K block of Bc rows); the
-    tables are then [B, Hkv, ceil(Nk/Bc), d]. Nk is taken from k's shape."""
+    tables are then [B, Hkv, ceil(Nk/Bc), d]. Nk is taken from k's shape. lse_out: float32
+    [B, H, N] that receives the rows' log-sum-exp (what a backward pass needs)."""
     B, H, Hkv, N, d = _shapes(q, k, v)
     Nk = k.shape[2]
     p = DaParams()
@@ -165,6 +169,12 @@ def make_params(q, k, v, Br, Bc=64, n_groups=None, causal=False, lsh_seed=0, n_p
     p.kt_in = kt_in.data_ptr() if kt_in is not None else None
     if kt_in is not None:
         _check_buffer(kt_in, "kt_in", distr_attn_kt_bytes(p))
+    if lse_out is not None:
+        import torch
+        if lse_out.dtype != torch.float32:
+            raise TypeError("lse_out must be float32")
+        _check_buffer(lse_out, "lse_out", 4 * B * H * N)
+        p.lse_out = lse_out.data_ptr()
     return p
 
 
@@ -224,6 +234,30 @@ def distr_attn_exact_fwd_ex(q, k, v, o, params):
     _check_ex(q, k, v, o, params)
     _check(lib().distr_attn_exact_fwd_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(o), ctypes.byref(params)))
     return o
+
+
+def _bwd(name, q, k, v, o, dout, lse, dq, dk, dv, params):
+    import torch
+    _check_ex(q, k, v, o, params)
+    _check_out(q, dout)
+    _check_out(q, dq)
+    _check_out(k, dk)
+    _check_out(k, dv)
+    if lse.dtype != torch.float32:
+        raise TypeError("lse must be float32")
+    _check_buffer(lse, "lse", 4 * params.B * params.H * params.N)
+    _check(getattr(lib(), name)(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(dout), _ptr(lse), _ptr(dq), _ptr(dk),
+                                _ptr(dv), ctypes.byref(params)))
+    return dq, dk, dv
+
+
+def distr_attn_bwd_ex(q, k, v, o, dout, lse, dq, dk, dv, params):
+    """Backward of distr_attn_fwd_ex (float path): fills dq, dk, dv. lse is the forward's lse_out."""
+    return _bwd("distr_attn_bwd_ex", q, k, v, o, dout, lse, dq, dk, dv, params)
+
+
+def distr_attn_exact_bwd_ex(q, k, v, o, dout, lse, dq, dk, dv, params):
+    return _bwd("distr_attn_exact_bwd_ex", q, k, v, o, dout, lse, dq, dk, dv, params)
 
 
 def distr_attn_lsh_group(q, params):

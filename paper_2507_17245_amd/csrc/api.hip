@@ -88,9 +88,13 @@ int resolve(const da_params* p, bool need_groups, Resolved* out) {
   } else if (p->Bc != 32 && p->Bc != 64 && p->Bc != 128) {
     return fail(DA_ERR_UNSUPPORTED, "Bc = %d: kernels are built for Bc in {32, 64, 128}", p->Bc);
   }
+  if (p->lse_out) {
+    if (mirrored) return fail(DA_ERR_UNSUPPORTED, "lse_out is not written by the mirrored form (side = 1)");
+    if (((uintptr_t)p->lse_out & 3u) != 0) return fail(DA_ERR_INVALID_ARG, "lse_out must be 4-byte aligned");
+  }
   if (need_groups && n_planes > da::kMaxPlanes) return fail(DA_ERR_UNSUPPORTED, "n_planes = %d > %d", n_planes, da::kMaxPlanes);
   out->pb = da::Problem{p->B, p->H, p->Hkv, p->N, p->d, p->Br, need_groups ? p->n_groups : p->d,
-                        p->causal, n_planes, p->gray_mode, p->lsh_seed, scale, Nk, mirrored ? 1 : 0, p->Bc};
+                        p->causal, n_planes, p->gray_mode, p->lsh_seed, scale, Nk, mirrored ? 1 : 0, p->Bc, p->lse_out};
   out->dtype = p->dtype;
   out->Tq = (p->N + p->Br - 1) / p->Br;
   out->Tk_side = (Nk + p->Bc - 1) / p->Bc;
@@ -259,6 +263,44 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
   return check_launch(e, "attention launch");
 }
 
+// Backward of the float path. The grouping is the forward's: the LSH stage runs again on q with
+// the same parameters (or the caller's perm_in is used), then the two gradient kernels.
+int attention_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
+                  void* dq, void* dk, void* dv, const da_params* p, bool distr) {
+  Resolved r;
+  int rc = resolve(p, distr, &r);
+  if (rc) return rc;
+  if (r.dtype != DA_F32) return fail(DA_ERR_UNSUPPORTED, "the backward pass is built for the float path only");
+  if (r.pb.side == 1) return fail(DA_ERR_UNSUPPORTED, "the backward pass is built for side = 0 only");
+  const void* in[] = {q, k, v, o, dout, lse};
+  void* out[] = {dq, dk, dv};
+  for (const void* x : in)
+    if (!x || !aligned16(x)) return fail(DA_ERR_INVALID_ARG, "q, k, v, o, dout, lse must be non-null and 16-byte aligned");
+  for (void* y : out) {
+    if (!y || !aligned16(y)) return fail(DA_ERR_INVALID_ARG, "dq, dk, dv must be non-null and 16-byte aligned");
+    for (const void* x : in)
+      if (x == y) return fail(DA_ERR_INVALID_ARG, "dq, dk, dv must not alias an input");
+  }
+  if (dq == dk || dq == dv || dk == dv) return fail(DA_ERR_INVALID_ARG, "dq, dk, dv must be distinct buffers");
+  const uint8_t* perm = nullptr;
+  if (distr) {
+    if (p->perm_in) {
+      perm = p->perm_in;
+    } else {
+      uint8_t* table = nullptr;
+      void* kt = nullptr;
+      rc = get_scratch(p, r, !p->perm_out, false, &table, &kt);
+      if (rc) return rc;
+      if (p->perm_out) table = p->perm_out;
+      rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, table, p->hash_out, r.stream), "lsh_group launch");
+      if (rc) return rc;
+      perm = table;
+    }
+  }
+  return check_launch(da::launch_attn_f32_bwd(q, k, v, o, dout, lse, dq, dk, dv, perm, r.pb, distr ? 1 : 0, r.stream),
+                      "backward launch");
+}
+
 da_params short_form(int B, int H, int Hkv, int N, int d, int Br, int Bc, int n_groups, uint64_t seed, int causal) {
   da_params p = {};
   p.B = B; p.H = H; p.Hkv = Hkv; p.N = N; p.d = d; p.Br = Br; p.Bc = Bc;
@@ -289,6 +331,16 @@ int distr_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, cons
 
 int distr_attn_exact_fwd_ex(const void* q, const void* k, const void* v, void* o, const da_params* p) {
   return attention(q, k, v, o, p, false);
+}
+
+int distr_attn_bwd_ex(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
+                      void* dq, void* dk, void* dv, const da_params* p) {
+  return attention_bwd(q, k, v, o, dout, lse, dq, dk, dv, p, true);
+}
+
+int distr_attn_exact_bwd_ex(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                            const float* lse, void* dq, void* dk, void* dv, const da_params* p) {
+  return attention_bwd(q, k, v, o, dout, lse, dq, dk, dv, p, false);
 }
 
 int distr_attn_fwd_noalloc(const void* q, const void* k, const void* v, void* o, const da_params* p) {

@@ -160,7 +160,7 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     bf16* __restrict__ o, const uint8_t* __restrict__ perm, const f16* __restrict__ kt, int Npad,
     int H, int Hkv, int N, int Nk, int Tq, int causal, float scale_log2e, int total_units, int n_planes,
-    int gray_mode, uint64_t lsh_seed) {
+    int gray_mode, uint64_t lsh_seed, float* __restrict__ lse) {
   using C = Cfg<D, BR, BC, KRED, DISTR, NG>;
   constexpr float kSumTrigger = (BC / 2) * 256.0f;   // BC/2 keys per lane and tile, each at most 2^kTau
   using kx8 = typename std::conditional<DISTR, f16x8, bf16x8>::type;
@@ -716,6 +716,8 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
   // ---- epilogue: O = O_acc / l, bf16, 8-byte stores ---------------------------------------------
   const float l_tot = half_swap_sum(l_run);
   const float inv = 1.0f / l_tot;
+  // row statistics for a backward pass: ln(sum of exp(score)) = ln 2 * (reference + log2(l))
+  if (lse && q_abs < N && hh == 0) lse[(size_t)bh * N + q_abs] = 0.6931471805599453f * (__builtin_log2f(l_tot) - nref);
   if (q_abs < N) {
     bf16* orow = o + ((size_t)bh * N + q_abs) * D;
 #pragma unroll
@@ -744,7 +746,7 @@ hipError_t launch_one(const void* q, const void* k, const void* v, void* o, cons
   hipLaunchKernelGGL((attn_bf16_kernel<D, BR, BC, KRED, DISTR, NG>), dim3((unsigned)units), dim3(BR * 2), 0,
                      stream, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, perm, (const f16*)kt,
                      (pb.Nk + kKtPad - 1) / kKtPad * kKtPad, pb.H, pb.Hkv, pb.N, pb.Nk, Tq, causal_mode,
-                     scale_log2e, (int)units, pb.n_planes, pb.gray_mode, pb.seed);
+                     scale_log2e, (int)units, pb.n_planes, pb.gray_mode, pb.seed, pb.lse);
   return hipGetLastError();
 }
 

@@ -24,7 +24,7 @@ template <int D, int BR>
 __global__ __launch_bounds__(BR * kF32Lanes) void attn_f32_kernel(
     const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ v,
     float* __restrict__ o, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Nk, int Tq,
-    int n_groups, int causal, float scale, int distr, int side, int Bc) {
+    int n_groups, int causal, float scale, int distr, int side, int Bc, float* __restrict__ lse) {
   constexpr int T = BR * kF32Lanes;
   constexpr int QS = D / kF32Lanes;            // most channels of the score product one lane takes
   constexpr int CS = D / kF32Lanes;            // output channels per lane
@@ -156,6 +156,7 @@ __global__ __launch_bounds__(BR * kF32Lanes) void attn_f32_kernel(
     }
   }
   if (active) {
+    if (lse && part == 0) lse[(size_t)bh * N + i_abs] = m_run + logf(l_run);   // row statistics for a backward pass
     float inv = 1.0f / l_run;
     float* orow = o + ((size_t)bh * N + i_abs) * D + part * CS;
 #pragma unroll
@@ -171,7 +172,7 @@ hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o,
 #define DA_F32_LAUNCH(DD, BB)                                                                      \
   hipLaunchKernelGGL((attn_f32_kernel<DD, BB>), grid, dim3(BB * kF32Lanes), 0, stream, (const float*)q,        \
                      (const float*)k, (const float*)v, (float*)o, perm, pb.H, pb.Hkv, pb.N, pb.Nk, Tq, \
-                     pb.n_groups, pb.causal, pb.scale, distr, pb.side, pb.Bc)
+                     pb.n_groups, pb.causal, pb.scale, distr, pb.side, pb.Bc, pb.lse)
   if (pb.d == 64 && pb.Br == 64) DA_F32_LAUNCH(64, 64);
   else if (pb.d == 64 && pb.Br == 128) DA_F32_LAUNCH(64, 128);
   else if (pb.d == 128 && pb.Br == 64) DA_F32_LAUNCH(128, 64);

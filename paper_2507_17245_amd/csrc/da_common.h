@@ -51,6 +51,7 @@ struct Problem {
   int side;   // 0: sample Q, fuse K, one grouping per Q block; 1: sample K, fuse Q, one grouping
               // per K block of Bc rows (float path only)
   int Bc;     // rows of a K block (only side 1 depends on it)
+  float* lse; // optional device [B][H][N]: log-sum-exp of every row's visible scores (natural log)
 };
 
 // Launchers (defined next to their kernels). All return hipError_t of the launch.
@@ -65,5 +66,10 @@ hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, void* o
 hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
                            const Problem& pb, int distr, hipStream_t stream);
 bool attn_bf16_supported(const Problem& pb, int distr);
+// Float backward: dq [B][H][N][d], dk and dv [B][Hkv][Nk][d] from the forward's inputs, its output
+// o, the output gradient dout and the forward's row statistics lse; perm as in launch_attn_f32.
+hipError_t launch_attn_f32_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                               const float* lse, void* dq, void* dk, void* dv, const uint8_t* perm,
+                               const Problem& pb, int distr, hipStream_t stream);
 
 }  // namespace da

@@ -15,10 +15,11 @@ def to_dev(x, dtype):
 
 
 def run_gpu(cfg, q, k, v, distr=True, want_tables=False, n_groups=None, lsh_seed=None, gray_mode=0,
-            scale=0.0, perm_in=None):
+            scale=0.0, perm_in=None, lse_out=None):
     """One forward through the C ABI. -> (o float64 numpy, perm uint8 or None, hash uint32 or None).
     scale 0 = the library's default 1/sqrt(d); perm_in: a grouping table (numpy uint8) to use
-    instead of the LSH stage."""
+    instead of the LSH stage; lse_out: a float32 device tensor [B, H, N] the call fills with the
+    rows' log-sum-exp."""
     tq, tk, tv = (to_dev(x, cfg.dtype) for x in (q, k, v))
     o = torch.full_like(tq, float("nan"))
     perm = hsh = None
@@ -31,7 +32,7 @@ def run_gpu(cfg, q, k, v, distr=True, want_tables=False, n_groups=None, lsh_seed
                        n_groups=cfg.n_groups if n_groups is None else n_groups, causal=cfg.causal,
                        lsh_seed=cfg.lsh_seed if lsh_seed is None else lsh_seed,
                        n_planes=cfg.n_planes, gray_mode=gray_mode, perm_out=perm, hash_out=hsh,
-                       softmax_scale=scale, perm_in=t_perm_in, side=cfg.side)
+                       softmax_scale=scale, perm_in=t_perm_in, side=cfg.side, lse_out=lse_out)
     if distr:
         da.distr_attn_fwd_ex(tq, tk, tv, o, p)
     else:

@@ -1,0 +1,100 @@
+"""GPU parity of the float backward pass against the CPU oracle (gradient of the forward with the
+grouping held fixed; the paper, Sec. 4.3-4.4, trains through the method without giving one)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4   # float path, relative to the larger of 1 and the gradient's largest magnitude
+
+CASES = [
+    ("one-block", dict(N=50)),
+    ("tiny", dict()),
+    ("ragged-causal", dict(N=150, causal=True)),
+    ("gqa-more-keys-causal", dict(H=4, Hkv=2, N=100, Nk=173, causal=True, Br=128)),
+    ("fewer-keys", dict(B=2, N=130, Nk=45)),
+    ("d128-groups-of-4", dict(H=2, Hkv=1, N=200, d=128, n_groups=32, Br=128, recipe="rho_pairs")),
+    ("blocks-of-256", dict(N=300, Br=256, causal=True, n_groups=16)),
+    ("one-channel-per-group", dict(N=90, n_groups=64, causal=True)),
+]
+
+
+def run_backward(cfg, q, k, v, dout, distr, perm_in=None):
+    import torch
+
+    import gpu_util as U
+    import paper_2507_17245_amd as da
+    tq, tk, tv, tdo = (U.to_dev(x, cfg.dtype) for x in (q, k, v, dout))
+    o = torch.full_like(tq, float("nan"))
+    lse = torch.full((cfg.B, cfg.H, cfg.N), float("nan"), dtype=torch.float32, device="cuda")
+    t_perm = None if perm_in is None else torch.from_numpy(np.ascontiguousarray(perm_in)).cuda()
+    p = da.make_params(tq, tk, tv, Br=cfg.Br, Bc=cfg.Bc, n_groups=cfg.n_groups, causal=cfg.causal,
+                       lsh_seed=cfg.lsh_seed, n_planes=cfg.n_planes, lse_out=lse, perm_in=t_perm)
+    fwd, bwd = (da.distr_attn_fwd_ex, da.distr_attn_bwd_ex) if distr else (da.distr_attn_exact_fwd_ex, da.distr_attn_exact_bwd_ex)
+    fwd(tq, tk, tv, o, p)
+    dq = torch.full_like(tq, float("nan"))
+    dk = torch.full_like(tk, float("nan"))
+    dv = torch.full_like(tk, float("nan"))
+    bwd(tq, tk, tv, o, tdo, lse, dq, dk, dv, p)
+    torch.cuda.synchronize()
+    return [t.cpu().numpy().astype(np.float64) for t in (dq, dk, dv)]
+
+
+@pytest.mark.parametrize("name,kw", CASES, ids=[c[0] for c in CASES])
+def test_backward_matches_oracle(name, kw):
+    import gpu_util as U
+    cfg = W.CONFIGS["tiny"].scaled(**kw)
+    print(f"case {cfg}", flush=True)
+    q, k, v = W.make(cfg)
+    dout = W.make_grad(cfg)
+    p = U.oracle_params(cfg)
+    for distr in (True, False):
+        got = run_backward(cfg, q, k, v, dout, distr)
+        ref = oracle.distr_bwd(q, k, v, dout, p) if distr else oracle.exact_bwd(q, k, v, dout, p)
+        for what, g, r in zip(("dq", "dk", "dv"), got, ref):
+            assert np.isfinite(g).all(), f"{what}: non-finite"
+            err = np.abs(g - r).max()
+            print(f"  distr={distr} {what}: max-abs {err:.3g} (largest gradient {np.abs(r).max():.3g})", flush=True)
+            assert err <= TOL * max(1.0, np.abs(r).max()), f"{name} distr={distr} {what}: {err:.4g}"
+        if distr and cfg.n_groups < cfg.d:
+            # the unsampled query columns of every block get exactly zero
+            _, perm, _ = oracle.lsh_group(q, p)
+            G = cfg.d // cfg.n_groups
+            for t in range(cfg.Tq):
+                unsampled = np.setdiff1d(np.arange(cfg.d), perm[0, 0, t, ::G])
+                assert np.all(got[0][0, 0, t * cfg.Br:(t + 1) * cfg.Br][:, unsampled] == 0.0)
+
+
+def test_backward_is_deterministic_and_takes_a_caller_table():
+    import gpu_util as U
+    cfg = W.CONFIGS["tiny"].scaled(H=2, Hkv=1, N=140, causal=True)
+    q, k, v = W.make(cfg)
+    dout = W.make_grad(cfg)
+    a = run_backward(cfg, q, k, v, dout, True)
+    b = run_backward(cfg, q, k, v, dout, True)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    _, perm, _ = oracle.lsh_group(q, U.oracle_params(cfg))
+    c = run_backward(cfg, q, k, v, dout, True, perm_in=perm)
+    assert all(np.array_equal(x, y) for x, y in zip(a, c))
+    rng = np.random.default_rng(5)
+    other = np.stack([rng.permutation(cfg.d) for _ in range(cfg.B * cfg.H * cfg.Tq)]).astype(np.uint8).reshape(cfg.B, cfg.H, cfg.Tq, cfg.d)
+    got = run_backward(cfg, q, k, v, dout, True, perm_in=other)
+    ref = oracle.distr_bwd(q, k, v, dout, U.oracle_params(cfg), perm=other)
+    for g, r in zip(got, ref):
+        assert np.abs(g - r).max() <= TOL * max(1.0, np.abs(r).max())
+
+
+def test_backward_is_refused_for_bf16():
+    import torch
+
+    import paper_2507_17245_amd as da
+    x = torch.zeros((1, 2, 64, 64), dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros((1, 2, 64), dtype=torch.float32, device="cuda")
+    outs = [torch.zeros_like(x) for _ in range(5)]
+    p = da.make_params(x, x, x, Br=64, n_groups=32)
+    with pytest.raises(da.DistrAttnError) as e:
+        da.distr_attn_bwd_ex(x, x, x, outs[0], outs[1], lse, outs[2], outs[3], outs[4], p)
+    assert e.value.code == da.DA_ERR_UNSUPPORTED

@@ -125,3 +125,28 @@ def test_head_major_causal_order_on_every_block():
     U.assert_close(o_gpu, oracle.distr_fwd(q, k, v, p), "bf16", "distr")
     o_ex, _, _ = U.run_gpu(cfg, q, k, v, distr=False)
     U.assert_close(o_ex, oracle.exact_fwd(q, k, v, p), "bf16", "exact")
+
+
+@pytest.mark.parametrize("base,kw", [("tiny", dict(N=150)), ("vit", dict(B=1, H=3, Hkv=3, N=150)),
+                                     ("llama", dict(H=4, Hkv=2, N=300, Nk=421)),
+                                     ("mid", dict(B=1, H=2, Hkv=2, N=260, Br=256, Bc=128))])
+def test_row_statistics_output(base, kw):
+    """lse_out: the logarithm of every row's softmax denominator (Sec. 2.2.2 keeps it as running
+    maximum and sum), for the approximate and the exact scores, against the oracle's."""
+    import torch
+
+    import gpu_util as U
+    cfg = small(base, **kw)
+    q, k, v = W.make(cfg)
+    p = U.oracle_params(cfg)
+    tol = 1e-4 if cfg.dtype == "f32" else 2e-2
+    for distr in (True, False):
+        lse = torch.full((cfg.B, cfg.H, cfg.N), float("nan"), dtype=torch.float32, device="cuda")
+        o, _, _ = U.run_gpu(cfg, q, k, v, distr=distr, lse_out=lse)
+        ref = oracle.lse(q, k, p, distr=distr)
+        err = np.abs(lse.cpu().numpy().astype(np.float64) - ref)
+        print(f"  {base} distr={distr}: lse max-abs {err.max():.3g}", flush=True)
+        assert err.max() <= tol
+        # asking for the statistics does not change the output
+        o2, _, _ = U.run_gpu(cfg, q, k, v, distr=distr)
+        assert np.array_equal(o, o2)

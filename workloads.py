@@ -145,6 +145,13 @@ def make(cfg: Config):
     return q, k, v
 
 
+def make_grad(cfg: Config):
+    """-> dout float32 [B, H, N, d]: a seeded N(0,1) output gradient for the backward-pass tests."""
+    rng = np.random.default_rng(cfg.data_seed + 4242)
+    g = _normal(rng, (cfg.B, cfg.H, cfg.N, cfg.d))
+    return round_to_bf16(g) if cfg.dtype == "bf16" else g
+
+
 def sample_tiles(cfg: Config, n_random=3, batch=0, heads=None):
     """Deterministic sample of Q blocks (b, h, t): first two, middle, last two and a few seeded
     random ones, for every head in `heads` (default: all) of one batch entry."""
