@@ -653,15 +653,39 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
     // ---- O^T += V^T . P^T: step tt covers keys 16*tt + {8*(j/4) + 4*hh + j%4} of the tile,
     // i.e. V rows 16*tt + 4*hh + 0..3 and 16*tt + 8 + 4*hh + 0..3.
     const char* vb = v_buf(par);
+    // The V operands are read PF steps (four operands) ahead of the MFMA that takes them, and the
+    // scheduler is told to keep that order: left alone it issues an operand's reads right in
+    // front of its MFMA, which then waits out the LDS latency 4 * TT times per tile.
+    constexpr int NMB = D / 32;
+    constexpr int PF = (4 / NMB < C::TT) ? 4 / NMB : C::TT - 1;
+    auto v_operand = [&](int tt, int mb) {
+      const char* p0 = vb + va_off[mb] + 16 * tt * C::ROWB;
+      return lds_read_tr_pair<bf16x8>(p0, p0 + 8 * C::ROWB);
+    };
+    bf16x8 va[PF + 1][NMB];
+#pragma unroll
+    for (int t0 = 0; t0 < PF; ++t0)
+#pragma unroll
+      for (int mb = 0; mb < NMB; ++mb) va[t0][mb] = v_operand(t0, mb);
 #pragma unroll
     for (int tt = 0; tt < C::TT; ++tt) {
+      if (tt + PF < C::TT) {
 #pragma unroll
-      for (int mb = 0; mb < D / 32; ++mb) {
-        const char* p0 = vb + va_off[mb] + 16 * tt * C::ROWB;
-        bf16x8 a = lds_read_tr_pair<bf16x8>(p0, p0 + 8 * C::ROWB);
-        oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pop[tt], oacc[mb], 0, 0, 0);
+        for (int mb = 0; mb < NMB; ++mb) va[(tt + PF) % (PF + 1)][mb] = v_operand(tt + PF, mb);
       }
+#pragma unroll
+      for (int mb = 0; mb < NMB; ++mb)
+        oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[tt % (PF + 1)][mb], pop[tt], oacc[mb], 0, 0, 0);
     }
+    // instruction order: the reads of the first PF steps, then every MFMA followed by the two
+    // reads of one operand PF steps ahead (0x100 = LDS reads, 0x008 = MFMA)
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * NMB * PF, 0);
+#pragma unroll
+    for (int i = 0; i < (C::TT - PF) * NMB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, PF * NMB, 0);
     if constexpr (HAS_NEXT) {
       if constexpr (decltype(mask_next_c)::value) apply_mask(it + 1, sn);
       dma_wait();              // this wave's direct loads have landed
