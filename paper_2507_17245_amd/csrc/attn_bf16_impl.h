@@ -272,69 +272,157 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
       static_assert(C::T % D == 0, "whole threads per channel");
       // (small tiles: the borrowed buffers are too short and the stage gets arrays of its own)
       constexpr bool R_BORROWS = BR * 16 * 4 <= C::TILEB, CODE_BORROWS = 2 * D * 4 <= C::KX_BYTES;
-      __shared__ float R_own[R_BORROWS ? 1 : BR * 16];
+      __shared__ float R_own[(R_BORROWS || QSTAGE) ? 1 : BR * 16];
       __shared__ uint32_t code_own[CODE_BORROWS ? 1 : 2 * D];
       float* R_lds = R_BORROWS ? (float*)v_lds0 : R_own;
       uint32_t* code_lds = CODE_BORROWS ? (uint32_t*)kx_lds0 : code_own;
       uint32_t* hash_lds = code_lds + D;
-      for (int i = tid; i < BR * 16; i += C::T)
-        R_lds[i] = (i & 15) < n_planes ? hyperplane_entry(lsh_seed, (uint32_t)(i & 15), (uint32_t)(i >> 4)) : 0.0f;
+      // Staged block: the projections are first taken on the matrix pipe, from R split into two
+      // bf16 pieces (an entry is an integer of 17 bits times 2^-16: r1 = R rounded to bf16 and
+      // r2 = R - r1 hold it exactly, and r1 + r2 gives it back exactly in float), next to
+      // sum |q| |r1|, which bounds how far that sum can be from the float sum that defines the
+      // sign. Only sums inside the bound are taken again the defining way (below). The pieces,
+      // [projection][row] with rows padded by 16 bytes (16 lanes read 16 rows at once), borrow
+      // the two V buffers where they fit.
+      constexpr int RPAD = BR + 8;
+      constexpr bool RP_BORROWS = 16 * RPAD * 2 <= C::TILEB;
+      __shared__ __attribute__((aligned(16))) bf16 rp_own[(QSTAGE && !RP_BORROWS) ? 2 : 1][(QSTAGE && !RP_BORROWS) ? 16 * RPAD : 1];
+      bf16* rp1 = RP_BORROWS ? (bf16*)v_lds0 : rp_own[0];
+      bf16* rp2 = RP_BORROWS ? (bf16*)v_lds1 : rp_own[(QSTAGE && !RP_BORROWS) ? 1 : 0];
+      if constexpr (QSTAGE) {
+        for (int i = tid; i < BR * 16; i += C::T) {
+          const int r = i % BR, pl = i / BR;
+          const float rv = pl < n_planes ? hyperplane_entry(lsh_seed, (uint32_t)pl, (uint32_t)r) : 0.0f;
+          const bf16 r1 = (bf16)rv;
+          rp1[pl * RPAD + r] = r1;
+          rp2[pl * RPAD + r] = (bf16)(rv - (float)r1);
+        }
+      } else {
+        for (int i = tid; i < BR * 16; i += C::T)
+          R_lds[i] = (i & 15) < n_planes ? hyperplane_entry(lsh_seed, (uint32_t)(i & 15), (uint32_t)(i >> 4)) : 0.0f;
+      }
       if (tid < D) code_lds[tid] = 0;
       if constexpr (QSTAGE) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of the Q block has landed
       __syncthreads();
       const int c = tid % D, pg = tid / D;
       const int rows = min(BR, N - r0);
       const bf16* qcol = qh + (size_t)r0 * D + c;
-      float acc[PPT];
-#pragma unroll
-      for (int j = 0; j < PPT; ++j) acc[j] = 0.0f;
-      // (not staged: 16 column loads in flight per thread, because with two workgroups per CU
-      // nothing else hides their latency here)
       if constexpr (QSTAGE) {
-        // Staged block: rows past N are zeros, and fma(0, R, acc) leaves acc as it is bit for bit,
-        // so all BR rows are walked (constant trip count); eight rows per step make the row's
-        // chunk exchange a constant of the unrolled step.
-        const char* col = q_stage + (c & 7) * 2;
-        int chunk_off[8];
+        // v_mfma_f32_16x16x32_bf16: 16 channels x 16 projections per product, 32 rows of the block
+        // per step; lane = (projection pl16 = lane % 16, row group kg = lane / 16) on the R side
+        // and (channel, row group) on the Q side, whose operand comes out of the staged block by
+        // transposing reads (rows past N are zeros there). Register i of the result belongs to
+        // channel 16*ct + 4*kg + i and projection pl16.
+        const int pl16 = lane & 15, kg = lane >> 4;
+        // The sign of a sum is taken from the matrix pipe only if the sum is further from zero
+        // than both roundings can reach, each relative to sum |q| |R| <= (1 + 2^-8) sum |q| |r1|:
+        // the pipe's, at most 2*BR products and BR/16 chained accumulators added in any order with
+        // any rounding direction (2 * (2*BR + BR/16) * 2^-24), and the defining float chain's,
+        // BR fused multiply-adds (BR * 2^-24). The absolute term covers products flushed to zero.
+        constexpr float kDoubt = 3.1e-7f * BR, kTiny = 1e-30f;
+        for (int ct = wave; ct < D / 16; ct += C::NW) {
+          f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f}, bnd = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int j8 = 0; j8 < 8; ++j8) chunk_off[j8] = j8 * C::ROWB + (((c >> 3) ^ (j8 & QSWZ)) << 4);
-#pragma unroll 2
-        for (int r8 = 0; r8 < BR; r8 += 8) {
+          for (int ks = 0; ks < BR / 32; ++ks) {
+            const int row0 = 32 * ks + 8 * kg + (pl16 >> 2), row1 = row0 + 4;
+            const int chunk = 2 * ct + ((pl16 & 3) >> 1), inch = 8 * (pl16 & 1);
+            const s16x8 a = lds_read_tr_pair<s16x8>(q_stage + row0 * C::ROWB + ((chunk ^ (row0 & QSWZ)) << 4) + inch,
+                                                    q_stage + row1 * C::ROWB + ((chunk ^ (row1 & QSWZ)) << 4) + inch);
+            const int roff = 32 * ks + 8 * kg;
+            const s16x8 b1 = *(const s16x8*)&rp1[pl16 * RPAD + roff];
+            const s16x8 b2 = *(const s16x8*)&rp2[pl16 * RPAD + roff];
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b1), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b2), acc, 0, 0, 0);
+            bnd = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a & (short)0x7fff),
+                                                          __builtin_bit_cast(bf16x8, b1 & (short)0x7fff), bnd, 0, 0, 0);
+          }
+          bool positive[4], doubt[4], any_doubt = false;
 #pragma unroll
-          for (int j8 = 0; j8 < 8; ++j8) {
-            const float x = (float)*(const bf16*)(col + r8 * C::ROWB + chunk_off[j8]);
+          for (int i = 0; i < 4; ++i) {
+            positive[i] = acc[i] > 0.0f;
+            doubt[i] = pl16 < n_planes && !(__builtin_fabsf(acc[i]) > kDoubt * bnd[i] + kTiny);
+            any_doubt |= doubt[i];
+          }
+          if (__builtin_amdgcn_ballot_w64(any_doubt) != 0) {
+            // The defining sums of this lane's four channels (float, one fused multiply-add per
+            // row, rows ascending): the channels 16*ct + 4*kg + 0..3 sit in one 8-byte piece of
+            // every staged row.
+            float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            const int ch0 = 16 * ct + 4 * kg;
+            const char* col = q_stage + (ch0 & 7) * 2;
+            int chunk_off[8];
 #pragma unroll
-            for (int j = 0; j < PPT; ++j)
-              acc[j] = __builtin_fmaf(x, R_lds[(r8 + j8) * 16 + pg * PPT + j], acc[j]);
+            for (int j8 = 0; j8 < 8; ++j8) chunk_off[j8] = j8 * C::ROWB + (((ch0 >> 3) ^ (j8 & QSWZ)) << 4);
+            for (int r8 = 0; r8 < BR; r8 += 8) {
+#pragma unroll
+              for (int j8 = 0; j8 < 8; ++j8) {
+                const s16x4 x4 = *(const s16x4*)(col + r8 * C::ROWB + chunk_off[j8]);
+                const float rv = (float)rp1[pl16 * RPAD + r8 + j8] + (float)rp2[pl16 * RPAD + r8 + j8];   // exact
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                  sum[i] = __builtin_fmaf(__builtin_bit_cast(float, (uint32_t)(uint16_t)x4[i] << 16), rv, sum[i]);
+              }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (doubt[i]) positive[i] = sum[i] > 0.0f;
+          }
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            // lanes 16*kg .. 16*kg + 15 of the ballot are projections 0..15 of channel 16*ct + 4*kg + i;
+            // projection 0 is the top bit of the n_planes-bit code
+            const uint64_t signs = __builtin_amdgcn_ballot_w64(positive[i]);
+            if (pl16 == 0)
+              code_lds[16 * ct + 4 * kg + i] = __builtin_bitreverse32((uint32_t)(signs >> (16 * kg)) & 0xffffu) >> (32 - n_planes);
           }
         }
       } else {
+        // (not staged: 16 column loads in flight per thread, because with two workgroups per CU
+        // nothing else hides their latency here)
+        float acc[PPT];
+#pragma unroll
+        for (int j = 0; j < PPT; ++j) acc[j] = 0.0f;
 #pragma unroll 16
         for (int r = 0; r < rows; ++r) {
           const float x = (float)qcol[(size_t)r * D];
 #pragma unroll
           for (int j = 0; j < PPT; ++j) acc[j] = __builtin_fmaf(x, R_lds[r * 16 + pg * PPT + j], acc[j]);
         }
-      }
-      uint32_t bits = 0;
+        uint32_t bits = 0;
 #pragma unroll
-      for (int j = 0; j < PPT; ++j) {
-        const int pl = pg * PPT + j;
-        if (pl < n_planes && acc[j] > 0.0f) bits |= 1u << (n_planes - 1 - pl);   // projection 0 = top bit
-      }
-      if (NPG == 1) code_lds[c] = bits;
-      else if (bits) atomicOr(&code_lds[c], bits);
-      __syncthreads();
-      if (tid < D) hash_lds[tid] = lsh_hash_of_code(code_lds[tid], gray_mode);
-      __syncthreads();
-      if (tid < D) {   // rank by counting = stable ascending sort; perm = inverse of the rank
-        const uint32_t mine = hash_lds[tid];
-        int rank = 0;
-        for (int o = 0; o < D; ++o) {
-          const uint32_t other = hash_lds[o];
-          rank += (other < mine || (other == mine && o < tid)) ? 1 : 0;
+        for (int j = 0; j < PPT; ++j) {
+          const int pl = pg * PPT + j;
+          if (pl < n_planes && acc[j] > 0.0f) bits |= 1u << (n_planes - 1 - pl);   // projection 0 = top bit
         }
-        perm_lds[rank] = (uint8_t)tid;
+        if (NPG == 1) code_lds[c] = bits;
+        else if (bits) atomicOr(&code_lds[c], bits);
+      }
+      __syncthreads();
+      if (tid < D) {
+        hash_lds[tid] = lsh_hash_of_code(code_lds[tid], gray_mode);
+        code_lds[tid] = 0;   // from here on the channel's rank is counted in this word
+      }
+      __syncthreads();
+      {
+        // Rank by counting = stable ascending sort; perm = inverse of the rank. Every thread
+        // counts a slice of the other channels for its own (NPG threads per channel, the hashes
+        // read four at a time), the slices meet in an integer LDS add.
+        constexpr int SL = D / NPG;
+        static_assert(SL % 4 == 0, "whole 16-byte reads per slice");
+        uint32_t* rank_lds = code_lds;
+        const int first = pg * SL;
+        const uint32_t mine = hash_lds[c];
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int o4 = 0; o4 < SL; o4 += 4) {
+          const u32x4 h = *(const u32x4*)&hash_lds[first + o4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) cnt += (h[j] < mine || (h[j] == mine && first + o4 + j < c)) ? 1u : 0u;
+        }
+        if (NPG == 1) rank_lds[c] = cnt;
+        else if (cnt) atomicAdd(&rank_lds[c], cnt);
+        __syncthreads();
+        if (tid < D) perm_lds[rank_lds[tid]] = (uint8_t)tid;
       }
     }
     if constexpr (QSTAGE) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
