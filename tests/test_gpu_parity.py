@@ -129,6 +129,44 @@ def test_degenerate_inputs():
         U.assert_close(o_gpu, oracle.exact_fwd(qd, k, v, p), "bf16", "dup vs oracle exact")
 
 
+@pytest.mark.parametrize("base,kw", [("vit", dict(B=1, H=2, Hkv=2, N=128)), ("llama", dict(H=2, Hkv=1, N=384)),
+                                     ("llama", dict(H=2, Hkv=1, N=300, Br=256)), ("mid", dict(B=1, H=1, Hkv=1, N=256))])
+def test_projections_that_nearly_cancel(base, kw):
+    """Columns built so that one projection of every channel sums to almost nothing (signs chosen
+    greedily against the running sum, the last rows sized to cancel what is left): the sign of
+    such a sum is decided by the rounding of the defining float chain, and the kernel must take
+    it that way too -- its matrix-pipe estimate is only trusted away from zero."""
+    U = _util()
+    import paper_2507_17245_amd as da
+    cfg = small(base, **kw)
+    q, k, v = W.make(cfg)
+    R = da.distr_attn_hyperplanes(cfg.lsh_seed, cfg.n_planes, cfg.Br).astype(np.float64)
+    for t in range(cfg.Tq):
+        r0, rows = t * cfg.Br, min(cfg.Br, cfg.N - t * cfg.Br)
+        for c in range(cfg.d):
+            w = R[c % cfg.n_planes, :rows]
+            col, run = np.zeros(rows), 0.0
+            for r in range(rows):
+                if r >= rows - 3 and abs(w[r]) > 0.1:      # closing rows: cancel the rest as well as bf16 allows
+                    col[r] = float(W.round_to_bf16(np.array([-run / w[r]], dtype=np.float32))[0])
+                else:
+                    col[r] = -1.0 if run * w[r] > 0 else 1.0
+                run += col[r] * w[r]
+            q[:, :, r0:r0 + rows, c] = col
+    p = U.oracle_params(cfg)
+    hash_ref, perm_ref, proj = oracle.lsh_group(q, p, want_proj=True)
+    near_zero = 0
+    for c in range(cfg.d):
+        near_zero += int((np.abs(proj[..., c, c % cfg.n_planes]) < 1e-4).sum())
+    print(f"  {near_zero} of {proj[..., 0].size} targeted sums are below 1e-4 (sum |q||R| is around {0.45 * cfg.Br:.0f})", flush=True)
+    assert near_zero > proj[..., 0].size // 2
+    o_gpu, perm_gpu, hash_gpu = U.run_gpu(cfg, q, k, v, distr=True, want_tables=True)
+    assert np.array_equal(hash_gpu, hash_ref) and np.array_equal(perm_gpu, perm_ref)
+    o_self, _, _ = U.run_gpu(cfg, q, k, v, distr=True, want_tables=False)    # the attention kernel's own LSH stage
+    assert np.array_equal(o_self, o_gpu), "in-kernel LSH and LSH kernel disagree"
+    U.assert_close(o_gpu, oracle.distr_fwd(q, k, v, p), cfg.dtype, "near-cancelling projections")
+
+
 def test_runs_are_deterministic_and_short_form_agrees():
     import torch
     import paper_2507_17245_amd as da
