@@ -131,9 +131,7 @@ da::Problem key_side_problem(const da::Problem& pb) {
 // Transposed half-precision copy of K that the bf16 distr path reads: [B][Hkv][d][Npad].
 size_t kt_bytes(const Resolved& r) {
   if (r.dtype != DA_BF16) return 0;
-  size_t npad = (size_t)((r.pb.Nk + da::kKtPad - 1) / da::kKtPad) * da::kKtPad;
-  size_t n = (size_t)r.pb.B * r.pb.Hkv * r.pb.d * npad * 2;
-  return (n + 255) & ~(size_t)255;
+  return da::kt_copy_bytes(r.pb.B, r.pb.Hkv, r.pb.d, r.pb.Nk) + da::kRtabBytes;
 }
 
 // Address of the static scratch array on the current device (looked up once per device).

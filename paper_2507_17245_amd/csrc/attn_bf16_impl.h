@@ -160,7 +160,7 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     bf16* __restrict__ o, const uint8_t* __restrict__ perm, const f16* __restrict__ kt, int Npad,
     int H, int Hkv, int N, int Nk, int Tq, int causal, float scale_log2e, int total_units, int n_planes,
-    int gray_mode, uint64_t lsh_seed, float* __restrict__ lse) {
+    int gray_mode, uint64_t lsh_seed, float* __restrict__ lse, const char* __restrict__ rtab) {
   using C = Cfg<D, BR, BC, KRED, DISTR, NG>;
   constexpr float kSumTrigger = (BC / 2) * 256.0f;   // BC/2 keys per lane and tile, each at most 2^kTau
   using kx8 = typename std::conditional<DISTR, f16x8, bf16x8>::type;
@@ -250,6 +250,22 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
                                                r0 * (D * 2), 0, 0);
     }
   };
+  // The two pieces of the projection table (each a whole number of 1 KB blocks) from the table in
+  // global memory into d1 and d2: block j of the 2 * PB blocks goes to wave j % NW.
+  auto load_rtab = [&](auto n_c, char* d1, char* d2) {
+    typedef __attribute__((address_space(3))) void lds_void_r;
+    constexpr int PB = ((16 * (BR + 8) * 2 + 1023) / 1024);
+    const __amdgpu_buffer_rsrc_t r_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(rtab + 1024), 0, 2 * PB * 1024, 0x00020000);
+#pragma unroll
+    for (int j = 0; j < decltype(n_c)::value; ++j) {
+      const int blk = j * (BR / 32) + wave;
+      if (blk < 2 * PB) {
+        char* dst = blk < PB ? d1 + blk * 1024 : d2 + (blk - PB) * 1024;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_rsrc, (lds_void_r*)dst, 16, lane * 16, blk * 1024, 0, 0);
+      }
+    }
+  };
   if constexpr (QSTAGE) {
     constexpr int QBLK = BR * C::ROWB / 1024;      // 1 KB blocks of the Q block
     static_assert(QBLK % C::NW == 0, "whole blocks per wave");
@@ -284,18 +300,31 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
       // sign. Only sums inside the bound are taken again the defining way (below). The pieces,
       // [projection][row] with rows padded by 16 bytes (16 lanes read 16 rows at once), borrow
       // the two V buffers where they fit.
+      // The pieces come from the table the key pre-pass left behind the K^T copy when its header
+      // names this call's seed, projection count and block rows (direct loads into LDS, no vector
+      // work); otherwise the workgroup generates them.
       constexpr int RPAD = BR + 8;
-      constexpr bool RP_BORROWS = 16 * RPAD * 2 <= C::TILEB;
-      __shared__ __attribute__((aligned(16))) bf16 rp_own[(QSTAGE && !RP_BORROWS) ? 2 : 1][(QSTAGE && !RP_BORROWS) ? 16 * RPAD : 1];
-      bf16* rp1 = RP_BORROWS ? (bf16*)v_lds0 : rp_own[0];
-      bf16* rp2 = RP_BORROWS ? (bf16*)v_lds1 : rp_own[(QSTAGE && !RP_BORROWS) ? 1 : 0];
+      constexpr int RP_BYTES = rtab_piece_bytes(BR);
+      constexpr bool RP_BORROWS = RP_BYTES <= C::TILEB;
+      __shared__ __attribute__((aligned(1024))) char rp_own[(QSTAGE && !RP_BORROWS) ? 2 : 1][(QSTAGE && !RP_BORROWS) ? RP_BYTES : 16];
+      bf16* rp1 = RP_BORROWS ? (bf16*)v_lds0 : (bf16*)rp_own[0];
+      bf16* rp2 = RP_BORROWS ? (bf16*)v_lds1 : (bf16*)rp_own[(QSTAGE && !RP_BORROWS) ? 1 : 0];
       if constexpr (QSTAGE) {
-        for (int i = tid; i < BR * 16; i += C::T) {
-          const int r = i % BR, pl = i / BR;
-          const float rv = pl < n_planes ? hyperplane_entry(lsh_seed, (uint32_t)pl, (uint32_t)r) : 0.0f;
-          const bf16 r1 = (bf16)rv;
-          rp1[pl * RPAD + r] = r1;
-          rp2[pl * RPAD + r] = (bf16)(rv - (float)r1);
+        bool have_table = false;
+        if (rtab != nullptr) {
+          const RtabHeader hd = *(const RtabHeader*)rtab;
+          have_table = hd.seed == lsh_seed && hd.n_planes == n_planes && hd.Br == BR;
+        }
+        if (have_table) {
+          load_rtab(std::integral_constant<int, (2 * (RP_BYTES / 1024) + C::NW - 1) / C::NW>(), (char*)rp1, (char*)rp2);
+        } else {
+          for (int i = tid; i < BR * 16; i += C::T) {
+            const int r = i % BR, pl = i / BR;
+            const float rv = pl < n_planes ? hyperplane_entry(lsh_seed, (uint32_t)pl, (uint32_t)r) : 0.0f;
+            const bf16 r1 = (bf16)rv;
+            rp1[pl * RPAD + r] = r1;
+            rp2[pl * RPAD + r] = (bf16)(rv - (float)r1);
+          }
         }
       } else {
         for (int i = tid; i < BR * 16; i += C::T)
@@ -858,7 +887,8 @@ hipError_t launch_one(const void* q, const void* k, const void* v, void* o, cons
   hipLaunchKernelGGL((attn_bf16_kernel<D, BR, BC, KRED, DISTR, NG>), dim3((unsigned)units), dim3(BR * 2), 0,
                      stream, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, perm, (const f16*)kt,
                      (pb.Nk + kKtPad - 1) / kKtPad * kKtPad, pb.H, pb.Hkv, pb.N, pb.Nk, Tq, causal_mode,
-                     scale_log2e, (int)units, pb.n_planes, pb.gray_mode, pb.seed, pb.lse);
+                     scale_log2e, (int)units, pb.n_planes, pb.gray_mode, pb.seed, pb.lse,
+                     (DISTR && kt) ? (const char*)kt + kt_copy_bytes(pb.B, pb.Hkv, pb.d, pb.Nk) : nullptr);
   return hipGetLastError();
 }
 

@@ -42,6 +42,24 @@ __host__ __device__ inline uint32_t lsh_hash_of_code(uint32_t code, int gray_mod
   return h;
 }
 
+// Behind the K^T copy the key pre-pass leaves the projection matrix of the LSH stage (Sec. 3.2),
+// split into two bf16 pieces r1 + r2 = R, for the attention kernel's own LSH stage at d = 64,
+// which otherwise generates it again in every workgroup: a header (seed, projections, block rows)
+// at offset 0 and, from offset kRtabHead on, the two pieces [16][Br + 8] bf16, each padded to a
+// whole number of 1 KB blocks (the unit of a direct load into LDS).
+struct RtabHeader {
+  uint64_t seed;
+  int32_t n_planes, Br;
+};
+constexpr int kRtabHead = 1024;
+constexpr int rtab_piece_bytes(int Br) { return (16 * (Br + 8) * 2 + 1023) / 1024 * 1024; }
+constexpr int kRtabBytes = kRtabHead + 2 * rtab_piece_bytes(256);
+// bytes of the K^T copy itself: [B][Hkv][d][Npad] half
+inline size_t kt_copy_bytes(int B, int Hkv, int d, int Nk) {
+  const size_t npad = (size_t)((Nk + kKtPad - 1) / kKtPad) * kKtPad;
+  return ((size_t)B * Hkv * d * npad * 2 + 255) & ~(size_t)255;
+}
+
 struct Problem {
   int B, H, Hkv, N, d, Br, n_groups, causal, n_planes, gray_mode;
   uint64_t seed;
@@ -57,10 +75,12 @@ struct Problem {
 // Launchers (defined next to their kernels). All return hipError_t of the launch.
 hipError_t launch_lsh_group(const void* q, int dtype, const Problem& pb, uint8_t* perm_out,
                             uint32_t* hash_out, hipStream_t stream);
-// K [B][Hkv][Nk][d] bf16 -> K^T [B][Hkv][d][Npad] half (Npad = Nk rounded up to kKtPad), for the distr path.
+// K [B][Hkv][Nk][d] bf16 -> K^T [B][Hkv][d][Npad] half (Npad = Nk rounded up to kKtPad), for the distr path,
+// followed at kt_copy_bytes() by the projection-matrix table (kRtabBytes) for pb's seed, n_planes and Br.
 hipError_t launch_kt_prepass(const void* k, void* kt, const Problem& pb, hipStream_t stream);
 // distr != 0: S^ = Q_r K_f^T with the per-block permutation table `perm` [B][H][Tq][d] and the
-// transposed keys `kt` written by launch_kt_prepass (k itself is then unused).
+// transposed keys `kt` written by launch_kt_prepass (k itself is then unused; the table behind the
+// copy is used when its header matches the call).
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
                             const void* kt, const Problem& pb, int distr, hipStream_t stream);
 hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,

@@ -227,6 +227,31 @@ def test_key_prepass_is_an_exact_transpose_and_kt_in_is_honoured():
     da.distr_attn_fwd_ex(tq, tk, tv, o2, da.make_params(tq, tk, tv, Br=cfg.Br, n_groups=cfg.n_groups, kt_in=kt))
     torch.cuda.synchronize()
     assert torch.equal(o1, o2)
+    # behind the copy: the projection matrix of the LSH stage (Sec. 3.2) for this call's seed,
+    # projection count and block rows, as two bf16 pieces that add up to it exactly
+    off = cfg.B * cfg.Hkv * cfg.d * npad * 2
+    head = kt[off:off + 16].cpu().numpy()
+    assert int(head[:8].view(np.uint64)[0]) == cfg.lsh_seed and head[8:16].view(np.int32).tolist() == [16, cfg.Br]
+    piece = (16 * (cfg.Br + 8) * 2 + 1023) // 1024 * 1024
+    both = kt[off + 1024:off + 1024 + 2 * piece].view(torch.bfloat16).float().cpu().numpy().reshape(2, piece // 2)
+    rp = both[:, :16 * (cfg.Br + 8)].reshape(2, 16, cfg.Br + 8)[:, :, :cfg.Br]
+    assert np.array_equal(rp[0] + rp[1], da.distr_attn_hyperplanes(cfg.lsh_seed, 16, cfg.Br))
+    # d = 64, where the attention kernel's own LSH stage reads that table: one made for another
+    # seed or block height is recognised by its header and not used
+    cfg = small("llama", H=4, Hkv=2, N=300)
+    q, k, v = W.make(cfg)
+    tq, tk, tv = (U.to_dev(x, "bf16") for x in (q, k, v))
+    common = dict(Br=cfg.Br, n_groups=cfg.n_groups, causal=True)
+    p = da.make_params(tq, tk, tv, **common)
+    o_ref = torch.empty_like(tq)
+    da.distr_attn_fwd_ex(tq, tk, tv, o_ref, p)
+    kt = torch.zeros(da.distr_attn_kt_bytes(p), dtype=torch.uint8, device="cuda")
+    for other in (dict(lsh_seed=7), dict(Br=64), dict(n_planes=8), dict()):
+        da.distr_attn_key_prepass(tk, kt, da.make_params(tq, tk, tv, **{**common, **other}))
+        o = torch.empty_like(tq)
+        da.distr_attn_fwd_ex(tq, tk, tv, o, da.make_params(tq, tk, tv, kt_in=kt, **common))
+        torch.cuda.synchronize()
+        assert torch.equal(o, o_ref), other
 
 
 def test_side_stream_and_back_to_back_calls():
