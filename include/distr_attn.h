@@ -149,10 +149,14 @@ int distr_attn_lsh_group(const void *q, const da_params *p);
 
 /*
  * Key pre-pass of the bf16 DistrAttention path alone: k [B][Hkv][Nk][d] bf16 -> kt_out
- * [B][Hkv][d][Npad] half, keys fastest, Npad = Nk rounded up to 64, tail zero-filled, values
+ * [B][Hkv][d][Npad] half, keys fastest, Npad = Nk rounded up to 128, tail zero-filled, values
  * clamped to +-65504/G* so that a group's sum (Sec. 3.2 fusion) stays finite in half. The fusion
- * then adds whole channel rows. distr_attn_fwd_ex runs it into its workspace unless kt_in is given.
- * kt_out: device, distr_attn_kt_bytes(p) bytes, 256-byte aligned.
+ * then adds whole channel rows. Behind the copy it leaves, in 19 KB, the projection matrix of the
+ * LSH stage (Sec. 3.2) for p's lsh_seed, n_planes and Br, which the attention kernel's own LSH stage
+ * loads instead of generating it in every workgroup; a forward whose seed, projection count or
+ * block rows differ from the table's header ignores the table, so a kt_in made with other values
+ * of those three stays valid. distr_attn_fwd_ex runs the pre-pass into its workspace unless kt_in
+ * is given. kt_out: device, distr_attn_kt_bytes(p) bytes, 256-byte aligned.
  */
 int distr_attn_key_prepass(const void *k, void *kt_out, const da_params *p);
 size_t distr_attn_kt_bytes(const da_params *p);

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kLshThreads) void lsh_group_kernel(
   constexpr int PPT = kMaxPlanes / NPG;       // plane slots per thread
   __shared__ float R_lds[kMaxLshRows * kMaxPlanes];   // [row][pg][j], zero where the plane does not exist
   __shared__ uint32_t code_lds[D];
-  __shared__ uint32_t hash_lds[D];
+  __shared__ __attribute__((aligned(16))) uint32_t hash_lds[D];
   __shared__ uint8_t perm_lds[D];
 
   const int tid = threadIdx.x;
@@ -88,17 +88,28 @@ __global__ __launch_bounds__(kLshThreads) void lsh_group_kernel(
   if (tid < D) {
     const uint32_t h = lsh_hash_of_code(code_lds[tid], gray_mode);
     hash_lds[tid] = h;
+    code_lds[tid] = 0;   // from here on the channel's rank is counted in this word
+    if (hash_out) hash_out[(size_t)blockIdx.x * D + tid] = h;
   }
   __syncthreads();
-  if (tid < D) {
-    const uint32_t mine = hash_lds[tid];
-    int rank = 0;
-    for (int o = 0; o < D; ++o) {
-      uint32_t other = hash_lds[o];
-      rank += (other < mine || (other == mine && o < tid)) ? 1 : 0;
+  {
+    // Rank by counting = stable ascending sort; perm = inverse of the rank. Every thread counts a
+    // slice of the other channels for its own (NPG threads per channel, hashes read four at a
+    // time); the slices meet in an integer LDS add.
+    constexpr int SL = D / NPG;
+    uint32_t* rank_lds = code_lds;
+    const int first = pg * SL;
+    const uint32_t mine = hash_lds[c];
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int o4 = 0; o4 < SL; o4 += 4) {
+      const u32x4 h = *(const u32x4*)&hash_lds[first + o4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) cnt += (h[j] < mine || (h[j] == mine && first + o4 + j < c)) ? 1u : 0u;
     }
-    perm_lds[rank] = (uint8_t)tid;
-    if (hash_out) hash_out[(size_t)blockIdx.x * D + tid] = mine;
+    if (cnt) atomicAdd(&rank_lds[c], cnt);
+    __syncthreads();
+    if (tid < D) perm_lds[rank_lds[tid]] = (uint8_t)tid;
   }
   __syncthreads();
   if (perm_out && tid < D) perm_out[(size_t)blockIdx.x * D + tid] = perm_lds[tid];
