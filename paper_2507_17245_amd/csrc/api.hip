@@ -1,6 +1,8 @@
 // C ABI of libdistr_attn.so: argument checks, workspace, launches. See include/distr_attn.h.
 #include "../../include/distr_attn.h"
 
+#include <cstdlib>
+
 #include <atomic>
 #include <cmath>
 #include <cstdarg>
@@ -200,8 +202,22 @@ int get_scratch(const da_params* p, const Resolved& r, bool need_table, bool no_
   return DA_OK;
 }
 
+// DISTR_ATTN_DEBUG=1 in the environment (read once): wait for the device after every launch, so
+// that a fault is reported by the call and the launch that caused it.
+bool debug_sync() {
+  static const bool on = [] {
+    const char* v = std::getenv("DISTR_ATTN_DEBUG");
+    return v != nullptr && v[0] == '1';
+  }();
+  return on;
+}
+
 int check_launch(hipError_t e, const char* what) {
   if (e != hipSuccess) return fail(DA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  if (debug_sync()) {
+    const hipError_t s = hipDeviceSynchronize();
+    if (s != hipSuccess) return fail(DA_ERR_HIP, "%s (found by DISTR_ATTN_DEBUG): %s", what, hipGetErrorString(s));
+  }
   return DA_OK;
 }
 

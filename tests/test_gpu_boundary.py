@@ -150,3 +150,16 @@ def test_row_statistics_output(base, kw):
         # asking for the statistics does not change the output
         o2, _, _ = U.run_gpu(cfg, q, k, v, distr=distr)
         assert np.array_equal(o, o2)
+
+
+def test_debug_mode_synchronises_after_every_launch():
+    """DISTR_ATTN_DEBUG=1 (read when the library is first called, hence a process of its own): the
+    small end-to-end check (LSH kernel, key pre-pass, both attention kernels) still passes."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, DISTR_ATTN_DEBUG="1")
+    res = subprocess.run([sys.executable, "-c", "import __graft_entry__ as g; g.smoke()"], cwd=root, env=env,
+                         capture_output=True, text=True, timeout=110)
+    assert res.returncode == 0, res.stdout[-2000:] + res.stderr[-2000:]
