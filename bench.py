@@ -23,9 +23,10 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak (published)
 
 
-# Registers per lane of the built attention kernels (exact kernel, from the compiler's resource
-# report), by (d, Bc); they do not depend on Br (a wave always owns 32 query rows).
-KERNEL_VGPRS = {(64, 32): 115, (64, 64): 161, (64, 128): 256, (128, 32): 167, (128, 64): 231, (128, 128): 402}
+# Registers per lane the attention kernel needs, by (d, Bc): the compiler's resource report for the
+# exact kernel built for Br = 128 (a wave always owns 32 query rows, so the need does not depend
+# on Br; the Br = 256, Bc = 128, d = 128 build is capped at 256 by its workgroup size and spills).
+KERNEL_VGPRS = {(64, 32): 114, (64, 64): 156, (64, 128): 246, (128, 32): 180, (128, 64): 240, (128, 128): 392}
 
 
 def block_size_rule(d):

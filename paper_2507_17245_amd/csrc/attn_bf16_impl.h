@@ -227,14 +227,13 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
   // (At d = 128 the stage is a percent of the block's time and the 32 KB are not spent.)
   constexpr bool QSTAGE = DISTR && D == 64;
   __shared__ __attribute__((aligned(1024))) char q_stage[QSTAGE ? BR * C::ROWB : 16];
-  // The 16-byte chunks of a staged row are exchanged by the row index (chunk ^ (row & 7)): the
-  // sampling reads one column of 32 different rows at once, which would otherwise all fall into
-  // one bank; reading a whole row (the LSH stage: lanes = channels) is conflict-free either way.
-  // (Blocks of 64 rows measured 5 % faster without the exchange -- their sampling is a small part
-  // of a prologue that the LSH stage dominates -- so it is applied from 128 rows on.)
-  constexpr int QSWZ = BR >= 128 ? 7 : 0;
+  // The 16-byte chunks of a staged row are exchanged by the row index (chunk ^ ((row >> 1) & 7);
+  // two rows of 128 bytes share a line of banks): the sampling reads one column of 32 different
+  // rows at once and the LSH stage's transposing reads four rows per 16 lanes, which would
+  // otherwise fall into one or two banks; reading along a row is conflict-free either way.
+  auto q_swz = [](int row) { return (row >> 1) & 7; };
   auto q_staged = [&](int row, int ch) -> bf16 {
-    return *(const bf16*)(q_stage + row * C::ROWB + (((ch >> 3) ^ (row & QSWZ)) << 4) + (ch & 7) * 2);
+    return *(const bf16*)(q_stage + row * C::ROWB + (((ch >> 3) ^ q_swz(row)) << 4) + (ch & 7) * 2);
   };
   // (a generic lambda, like the other direct loads below: the builtins exist for the device only,
   // and a template is not checked against the host's builtin set)
@@ -246,7 +245,7 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
       const int blk = j * C::NW + wave;
       const int slot = blk * 64 + lane;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(q_rsrc, (lds_void_q*)(dst + blk * 1024), 16,
-                                               (slot / (D / 8)) * (D * 2) + ((slot % (D / 8)) ^ ((slot / (D / 8)) & (BR >= 128 ? 7 : 0))) * 16,
+                                               (slot / (D / 8)) * (D * 2) + ((slot % (D / 8)) ^ (((slot / (D / 8)) >> 1) & 7)) * 16,
                                                r0 * (D * 2), 0, 0);
     }
   };
@@ -355,8 +354,8 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
           for (int ks = 0; ks < BR / 32; ++ks) {
             const int row0 = 32 * ks + 8 * kg + (pl16 >> 2), row1 = row0 + 4;
             const int chunk = 2 * ct + ((pl16 & 3) >> 1), inch = 8 * (pl16 & 1);
-            const s16x8 a = lds_read_tr_pair<s16x8>(q_stage + row0 * C::ROWB + ((chunk ^ (row0 & QSWZ)) << 4) + inch,
-                                                    q_stage + row1 * C::ROWB + ((chunk ^ (row1 & QSWZ)) << 4) + inch);
+            const s16x8 a = lds_read_tr_pair<s16x8>(q_stage + row0 * C::ROWB + ((chunk ^ q_swz(row0)) << 4) + inch,
+                                                    q_stage + row1 * C::ROWB + ((chunk ^ q_swz(row1)) << 4) + inch);
             const int roff = 32 * ks + 8 * kg;
             const s16x8 b1 = *(const s16x8*)&rp1[pl16 * RPAD + roff];
             const s16x8 b2 = *(const s16x8*)&rp2[pl16 * RPAD + roff];
@@ -379,13 +378,10 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
             float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
             const int ch0 = 16 * ct + 4 * kg;
             const char* col = q_stage + (ch0 & 7) * 2;
-            int chunk_off[8];
-#pragma unroll
-            for (int j8 = 0; j8 < 8; ++j8) chunk_off[j8] = j8 * C::ROWB + (((ch0 >> 3) ^ (j8 & QSWZ)) << 4);
             for (int r8 = 0; r8 < BR; r8 += 8) {
 #pragma unroll
               for (int j8 = 0; j8 < 8; ++j8) {
-                const s16x4 x4 = *(const s16x4*)(col + r8 * C::ROWB + chunk_off[j8]);
+                const s16x4 x4 = *(const s16x4*)(col + (r8 + j8) * C::ROWB + (((ch0 >> 3) ^ q_swz(r8 + j8)) << 4));
                 const float rv = (float)rp1[pl16 * RPAD + r8 + j8] + (float)rp2[pl16 * RPAD + r8 + j8];   // exact
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
