@@ -20,6 +20,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
+PEAK_FP32_TFLOPS = 157.3   # MI355X fp32 vector peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak (published)
 
 
@@ -224,6 +225,47 @@ def main():
                 "best_distr": [best_d["Br"], best_d["Bc"]], "best_exact": [best_e["Br"], best_e["Bc"]],
                 "rule_pick": list(rule)}
 
+    def float_path_table(steps):
+        """The float (reference-precision) path on a shape large enough to fill the chip: forward,
+        the mirrored form that samples K and fuses Q (Sec. 3.1, Fig. 4 right), and the backward
+        pass (gradient with the grouping held fixed), each with the exact counterpart and the
+        executed FLOPs against the fp32 vector peak (these kernels are built for accuracy checks)."""
+        cfg = W.CONFIGS["tiny"].scaled(name="float", H=8, Hkv=8, N=2048, Br=128, n_planes=16, recipe="normal")
+        q, k, v = (to_dev(x, "f32") for x in W.make(cfg))
+        dout = to_dev(W.make_grad(cfg), "f32")
+        o = torch.empty_like(q)
+        lse = torch.empty((cfg.B, cfg.H, cfg.N), dtype=torch.float32, device=dev)
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(k)
+        common = dict(Br=cfg.Br, Bc=cfg.Bc, causal=cfg.causal, n_planes=cfg.n_planes, lsh_seed=cfg.lsh_seed)
+        p_d = da.make_params(q, k, v, n_groups=cfg.n_groups, lse_out=lse, **common)
+        p_e = da.make_params(q, k, v, lse_out=lse, **common)
+        p_m = da.make_params(q, k, v, n_groups=cfg.n_groups, side=1, **common)
+        pairs = cfg.B * cfg.H * visible_pairs(cfg.N, cfg.causal)
+        fl_d, fl_e = 2.0 * pairs * (cfg.n_groups + cfg.d), 4.0 * pairs * cfg.d
+        runs = {
+            "forward": (lambda: da.distr_attn_fwd_ex(q, k, v, o, p_d), fl_d),
+            "forward_exact": (lambda: da.distr_attn_exact_fwd_ex(q, k, v, o, p_e), fl_e),
+            "forward_mirrored": (lambda: da.distr_attn_fwd_ex(q, k, v, o, p_m), fl_d),
+        }
+        out = {"workload": f"float: B={cfg.B} H={cfg.H} N={cfg.N} d={cfg.d} f32 non-causal Br={cfg.Br} Bc={cfg.Bc} "
+                           f"n_groups={cfg.n_groups}", "peak_fp32_tflops": PEAK_FP32_TFLOPS}
+        for name, (fn, fl) in runs.items():
+            fn()
+            ms = ev_time(fn, steps)
+            out[name] = {"ms": ms, "alu_frac": fl / (ms * 1e-3) / 1e12 / PEAK_FP32_TFLOPS}
+        # backward: two kernels (dQ; dK and dV), each rebuilds the scores and dP: 2 * (2k + 2d) FLOP per pair and kernel
+        da.distr_attn_fwd_ex(q, k, v, o, p_d)
+        bw_d = lambda: da.distr_attn_bwd_ex(q, k, v, o, dout, lse, dq, dk, dv, p_d)
+        bw_d()
+        ms = ev_time(bw_d, steps)
+        out["backward"] = {"ms": ms, "alu_frac": 4.0 * fl_d / (ms * 1e-3) / 1e12 / PEAK_FP32_TFLOPS}
+        da.distr_attn_exact_fwd_ex(q, k, v, o, p_e)
+        bw_e = lambda: da.distr_attn_exact_bwd_ex(q, k, v, o, dout, lse, dq, dk, dv, p_e)
+        bw_e()
+        ms = ev_time(bw_e, steps)
+        out["backward_exact"] = {"ms": ms, "alu_frac": 4.0 * fl_e / (ms * 1e-3) / 1e12 / PEAK_FP32_TFLOPS}
+        return out
+
     results = {}
     head_cfg = W.CONFIGS[args.workload]
     order = [args.workload] if args.only else [n for n in ("vit", "llama", "mid", "long", "tiny")]
@@ -254,6 +296,10 @@ def main():
             head_inputs = host
         del tensors
         torch.cuda.empty_cache()
+
+    if not args.only:
+        results["float_path"] = float_path_table(max(3, args.steps // 4))
+        log(f"[bench] float path: " + ", ".join(f"{k} {v['ms']:.3f} ms" for k, v in results["float_path"].items() if isinstance(v, dict)))
 
     head = results[f"{args.workload}_k{head_cfg.n_groups}"]
 
