@@ -35,6 +35,24 @@ def test_other_key_count(Nq, Nk, causal):
         U.assert_close(o_ex, oracle.exact_fwd(q, k, v, p), cfg.dtype, "exact")
 
 
+@pytest.mark.parametrize("Nq", [1, 200])
+def test_decode_against_a_full_length_cache(Nq):
+    """A few queries against the key count of the largest configuration (N_k = 32768, d = 128, and
+    N_k = 16384 at d = 64 with grouped heads): the shape of decoding against a cache, every row
+    against the oracle."""
+    import gpu_util as U
+    for base, kw in (("long", dict(H=4, Hkv=2, Nk=32768)), ("llama", dict(H=8, Hkv=2, Nk=16384))):
+        cfg = small(base, N=Nq, causal=True, data_seed=7100 + Nq, **kw)
+        q, k, v = W.make(cfg)
+        p = U.oracle_params(cfg)
+        print(f"case {cfg}", flush=True)
+        o_gpu, perm_gpu, _ = U.run_gpu(cfg, q, k, v, distr=True, want_tables=True)
+        assert np.array_equal(perm_gpu, U.oracle_tables(cfg, q, k)[1])
+        U.assert_close(o_gpu, oracle.distr_fwd(q, k, v, p), cfg.dtype, "distr")
+        o_ex, _, _ = U.run_gpu(cfg, q, k, v, distr=False)
+        U.assert_close(o_ex, oracle.exact_fwd(q, k, v, p), cfg.dtype, "exact")
+
+
 @pytest.mark.parametrize("Nq,Nk,causal", [(1, 200, False), (64, 300, True), (150, 150, True), (300, 70, False)])
 def test_other_key_count_float_path(Nq, Nk, causal):
     import gpu_util as U
