@@ -104,6 +104,17 @@ def test_gray_modes_seeds_and_plane_counts():
         o_tab, _, _ = U.run_gpu(c, q, k, v, distr=True, want_tables=True, gray_mode=gray_mode)
         o_self, _, _ = U.run_gpu(c, q, k, v, distr=True, want_tables=False, gray_mode=gray_mode)
         assert np.array_equal(o_tab, o_self), (gray_mode, planes, seed)
+    # d = 64: the attention kernel's own stage takes the projections on the matrix pipe
+    for base, kw in (("vit", dict(B=1, H=3, Hkv=3, N=200)), ("llama", dict(H=4, Hkv=2, N=400))):
+        cfg64 = small(base, **kw)
+        q, k, v = W.make(cfg64)
+        for gray_mode, planes, seed in ((0, 1, 0), (1, 4, 3), (0, 7, 12345678901234567), (1, 16, 5), (0, 15, 2 ** 63 + 11)):
+            c = cfg64.scaled(n_planes=planes, lsh_seed=seed)
+            o_tab, perm_gpu, hash_gpu = U.run_gpu(c, q, k, v, distr=True, want_tables=True, gray_mode=gray_mode)
+            hash_ref, perm_ref, _ = oracle.lsh_group(q, U.oracle_params(c, gray_mode=gray_mode))
+            assert np.array_equal(hash_gpu, hash_ref) and np.array_equal(perm_gpu, perm_ref), (base, gray_mode, planes, seed)
+            o_self, _, _ = U.run_gpu(c, q, k, v, distr=True, want_tables=False, gray_mode=gray_mode)
+            assert np.array_equal(o_tab, o_self), (base, gray_mode, planes, seed)
 
 
 def test_degenerate_inputs():
