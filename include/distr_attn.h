@@ -14,7 +14,7 @@
  *   - Calls only enqueue work on the stream (asynchronous); they never synchronise the device
  *     (distr_attn_release does). Debugging aid: with DISTR_ATTN_DEBUG=1 in the environment when the
  *     library is first called, every launch is followed by a device synchronisation and a fault is
- *     reported by the call that caused it, naming the launch (not for use under graph capture).
+ *     reported by the call that caused it, naming the launch (launches into a stream under capture are not waited for).
  *   - Return value: DA_OK or a negative da_status. All argument checks run on the host before
  *     anything is launched; on error nothing has been enqueued. distr_attn_last_error() gives a
  *     message for the last failure on the calling thread.

@@ -212,9 +212,10 @@ bool debug_sync() {
   return on;
 }
 
-int check_launch(hipError_t e, const char* what) {
+int check_launch(hipError_t e, const char* what, hipStream_t stream) {
   if (e != hipSuccess) return fail(DA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
-  if (debug_sync()) {
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (debug_sync() && hipStreamIsCapturing(stream, &cap) == hipSuccess && cap == hipStreamCaptureStatusNone) {
     const hipError_t s = hipDeviceSynchronize();
     if (s != hipSuccess) return fail(DA_ERR_HIP, "%s (found by DISTR_ATTN_DEBUG): %s", what, hipGetErrorString(s));
   }
@@ -239,7 +240,7 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
   const bool trivial_groups = distr && r.dtype == DA_BF16 && p->n_groups == p->d;
   if (trivial_groups) {
     if (!p->perm_in && (p->perm_out || p->hash_out)) {
-      rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, p->perm_out, p->hash_out, r.stream), "lsh_group launch");
+      rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, p->perm_out, p->hash_out, r.stream), "lsh_group launch", r.stream);
       if (rc) return rc;
     }
     distr = false;
@@ -259,7 +260,7 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
       rc = check_launch(r.pb.side == 1
                             ? da::launch_lsh_group(k, r.dtype, key_side_problem(r.pb), table, p->hash_out, r.stream)
                             : da::launch_lsh_group(q, r.dtype, r.pb, table, p->hash_out, r.stream),
-                        "lsh_group launch");
+                        "lsh_group launch", r.stream);
       if (rc) return rc;
       perm = table;
     }
@@ -267,14 +268,14 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
       if (((uintptr_t)p->kt_in & 255u) != 0) return fail(DA_ERR_INVALID_ARG, "kt_in must be 256-byte aligned");
       kt = const_cast<void*>(p->kt_in);
     } else if (r.dtype == DA_BF16) {
-      rc = check_launch(da::launch_kt_prepass(k, kt, r.pb, r.stream), "key pre-pass launch");
+      rc = check_launch(da::launch_kt_prepass(k, kt, r.pb, r.stream), "key pre-pass launch", r.stream);
       if (rc) return rc;
     }
   }
   hipError_t e = (r.dtype == DA_BF16)
                      ? da::launch_attn_bf16(q, k, v, o, perm, kt, r.pb, distr ? 1 : 0, r.stream)
                      : da::launch_attn_f32(q, k, v, o, perm, r.pb, distr ? 1 : 0, r.stream);
-  return check_launch(e, "attention launch");
+  return check_launch(e, "attention launch", r.stream);
 }
 
 // Backward of the float path. The grouping is the forward's: the LSH stage runs again on q with
@@ -306,13 +307,13 @@ int attention_bwd(const void* q, const void* k, const void* v, const void* o, co
       rc = get_scratch(p, r, !p->perm_out, false, &table, &kt);
       if (rc) return rc;
       if (p->perm_out) table = p->perm_out;
-      rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, table, p->hash_out, r.stream), "lsh_group launch");
+      rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, table, p->hash_out, r.stream), "lsh_group launch", r.stream);
       if (rc) return rc;
       perm = table;
     }
   }
   return check_launch(da::launch_attn_f32_bwd(q, k, v, o, dout, lse, dq, dk, dv, perm, r.pb, distr ? 1 : 0, r.stream),
-                      "backward launch");
+                      "backward launch", r.stream);
 }
 
 da_params short_form(int B, int H, int Hkv, int N, int d, int Br, int Bc, int n_groups, uint64_t seed, int causal) {
@@ -371,7 +372,7 @@ int distr_attn_lsh_group(const void* q, const da_params* p) {
   if (!p->perm_out && !p->hash_out) return fail(DA_ERR_INVALID_ARG, "perm_out or hash_out must be given");
   // side 1: the tensor is K ([B][Hkv][Nk][d]) and the blocks are its Bc-row K blocks
   return check_launch(da::launch_lsh_group(q, r.dtype, r.pb.side == 1 ? key_side_problem(r.pb) : r.pb, p->perm_out,
-                                           p->hash_out, r.stream), "lsh_group launch");
+                                           p->hash_out, r.stream), "lsh_group launch", r.stream);
 }
 
 int distr_attn_key_prepass(const void* k, void* kt_out, const da_params* p) {
@@ -382,7 +383,7 @@ int distr_attn_key_prepass(const void* k, void* kt_out, const da_params* p) {
   if (r.dtype != DA_BF16) return fail(DA_ERR_UNSUPPORTED, "the key pre-pass belongs to the bf16 path");
   if (((uintptr_t)k & 15u) != 0 || ((uintptr_t)kt_out & 255u) != 0)
     return fail(DA_ERR_INVALID_ARG, "k must be 16-byte and kt_out 256-byte aligned");
-  return check_launch(da::launch_kt_prepass(k, kt_out, r.pb, r.stream), "key pre-pass launch");
+  return check_launch(da::launch_kt_prepass(k, kt_out, r.pb, r.stream), "key pre-pass launch", r.stream);
 }
 
 size_t distr_attn_kt_bytes(const da_params* p) {
