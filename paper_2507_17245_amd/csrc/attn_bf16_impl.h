@@ -26,7 +26,9 @@
 // Pipeline (one barrier per tile): K (exact) and V tiles reach LDS by direct global->LDS loads
 // two tiles (K) / one tile (V) ahead, the K^T pieces of the fusion reach registers one tile
 // ahead of their use; while the vector ALUs exponentiate tile i the matrix pipe computes the
-// scores of tile i+1; P.V of tile i runs beside the row maximum of tile i+1.
+// scores of tile i+1; P.V of tile i follows with its V operands read four ahead of their MFMAs.
+// The reference of the online softmax moves only when a tile's row sum says it must (no row
+// maximum per tile).
 #pragma once
 #include <type_traits>
 
@@ -277,11 +279,14 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
       for (int i = tid; i < D; i += C::T) perm_lds[i] = perm[pbase + i] & (D - 1);
     } else {
       // ---- LSH hash-and-group of this Q block inside the workgroup (Sec. 3.2, 3.3) -------------
-      // Same arithmetic as the stand-alone LSH kernel (float, one fused multiply-add per row,
-      // rows ascending, from +0), so the table equals that kernel's bit for bit; here it costs
-      // no launch, no table in HBM, and runs while the CU's other workgroup keeps the matrix
-      // pipes busy. Up to 16 projections: R[row][16] borrows the first V buffer (8 KB), the
-      // codes and hashes borrow the first Kx buffer; both are filled only after the barriers below.
+      // The table equals the stand-alone LSH kernel's bit for bit: a projection's sign is that of
+      // the float sum with one fused multiply-add per row, rows ascending, from +0. At d = 128 the
+      // sums are taken exactly that way; at d = 64 the matrix pipe takes them first and the defining
+      // sum is only redone where the pipe's result is too close to zero to decide (below). Here the
+      // stage costs no launch and no table in HBM, and runs while the CU's other workgroups keep
+      // the matrix pipes busy. Up to 16 projections: R[row][16] (d = 128) or its two bf16 pieces
+      // (d = 64) borrow the V buffers, the codes and hashes the first Kx buffer; all are filled
+      // only after the barriers below.
       constexpr int NPG = C::T / D;             // threads per channel
       constexpr int PPT = 16 / NPG;             // projections per thread: pg*PPT .. pg*PPT+PPT-1
       static_assert(C::T % D == 0, "whole threads per channel");
