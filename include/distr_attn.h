@@ -119,7 +119,9 @@ int distr_attn_fwd_ex(const void *q, const void *k, const void *v, void *o, cons
 int distr_attn_exact_fwd_ex(const void *q, const void *k, const void *v, void *o, const da_params *p);
 
 /*
- * Backward pass of the two calls above, float path only (dtype = DA_F32, side = 0). The paper
+ * Backward pass of the two calls above (side = 0), in float arithmetic on the vector ALUs for both
+ * dtypes: float tensors, or bf16 tensors converted on load and rounded on store (a
+ * reference-speed path; there is no matrix-core backward). The paper
  * trains through the method (Sec. 4.3, 4.4) without giving a gradient; computed here is the
  * derivative of the forward with every query block's grouping held fixed (the grouping is a
  * piecewise-constant function of q): with P = softmax(S^), dP = dout V^T, D_i = sum_c dout_ic o_ic
@@ -128,11 +130,11 @@ int distr_attn_exact_fwd_ex(const void *q, const void *k, const void *v, void *o
  * (dS^T Q_r)[:, group of c in that block]  (Q_r, K_f: sampled and fused columns, Sec. 3.2, Eq. 2).
  * The exact call is the case of one channel per group (Sec. 2.1).
  * q, k, v, p: as given to the forward; o: its output; lse: its lse_out; dout [B][H][N][d]: gradient
- * of the loss with respect to o. Written: dq [B][H][N][d], dk and dv [B][Hkv][Nk][d] (float, device,
- * 16-byte aligned, distinct from every input and from each other). The grouping is recomputed
+ * of the loss with respect to o, same dtype. Written: dq [B][H][N][d], dk and dv [B][Hkv][Nk][d]
+ * (p->dtype, device, 16-byte aligned, distinct from every input and from each other). The grouping is recomputed
  * from q (same seed and options give the forward's table) unless p->perm_in brings it; the table
  * lives in the workspace as in the forward. No atomics: results are the same on every run.
- * Errors: as the forward; DA_ERR_UNSUPPORTED for bf16 or side = 1.
+ * Errors: as the forward; DA_ERR_UNSUPPORTED for side = 1.
  */
 int distr_attn_bwd_ex(const void *q, const void *k, const void *v, const void *o, const void *dout,
                       const float *lse, void *dq, void *dk, void *dv, const da_params *p);

@@ -285,7 +285,6 @@ int attention_bwd(const void* q, const void* k, const void* v, const void* o, co
   Resolved r;
   int rc = resolve(p, distr, &r);
   if (rc) return rc;
-  if (r.dtype != DA_F32) return fail(DA_ERR_UNSUPPORTED, "the backward pass is built for the float path only");
   if (r.pb.side == 1) return fail(DA_ERR_UNSUPPORTED, "the backward pass is built for side = 0 only");
   const void* in[] = {q, k, v, o, dout, lse};
   void* out[] = {dq, dk, dv};
@@ -312,7 +311,7 @@ int attention_bwd(const void* q, const void* k, const void* v, const void* o, co
       perm = table;
     }
   }
-  return check_launch(da::launch_attn_f32_bwd(q, k, v, o, dout, lse, dq, dk, dv, perm, r.pb, distr ? 1 : 0, r.stream),
+  return check_launch(da::launch_attn_f32_bwd(q, k, v, o, dout, lse, dq, dk, dv, perm, r.pb, r.dtype, distr ? 1 : 0, r.stream),
                       "backward launch", r.stream);
 }
 

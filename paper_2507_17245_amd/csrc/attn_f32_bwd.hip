@@ -1,5 +1,6 @@
-// Float backward of the attention forward (exact and DistrAttention) for gfx950: the
-// reference-precision path, two kernels, no atomics (results do not depend on the run).
+// Backward of the attention forward (exact and DistrAttention) for gfx950 in float arithmetic on
+// the vector ALUs: the reference-precision path, for float tensors and (converted on load, rounded
+// on store) for bf16 tensors; two kernels, no atomics (results do not depend on the run).
 //
 // The paper trains through the approximation (Sec. 4.3, 4.4) and gives no gradient. Computed
 // here: the derivative of the forward with every Q block's grouping held fixed (the permutation
@@ -31,11 +32,11 @@ __device__ inline float quad_sum(float x) {
   return x;
 }
 
-template <int D, int BR>
+template <typename E, int D, int BR>
 __global__ __launch_bounds__(BR * kBwdLanes) void attn_f32_bwd_dq_kernel(
-    const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ v,
-    const float* __restrict__ o, const float* __restrict__ dout, const float* __restrict__ lse,
-    float* __restrict__ dq, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Nk, int Tq,
+    const E* __restrict__ q, const E* __restrict__ k, const E* __restrict__ v,
+    const E* __restrict__ o, const E* __restrict__ dout, const float* __restrict__ lse,
+    E* __restrict__ dq, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Nk, int Tq,
     int n_groups, int causal, float scale, int distr) {
   constexpr int T = BR * kBwdLanes;
   constexpr int QS = D / kBwdLanes;   // most columns of the score product one lane takes
@@ -58,8 +59,8 @@ __global__ __launch_bounds__(BR * kBwdLanes) void attn_f32_bwd_dq_kernel(
   const int G = D / kred;
   const int shift = Nk - N;   // causal: key n is visible to query i iff n <= i + shift
 
-  const float* kh = k + ((size_t)(b * Hkv + hk) * Nk) * D;
-  const float* vh = v + ((size_t)(b * Hkv + hk) * Nk) * D;
+  const E* kh = k + ((size_t)(b * Hkv + hk) * Nk) * D;
+  const E* vh = v + ((size_t)(b * Hkv + hk) * Nk) * D;
 
   for (int i = tid; i < D; i += T) {
     perm_lds[i] = distr ? (perm[(size_t)blockIdx.x * D + i] & (D - 1)) : (uint8_t)i;
@@ -76,14 +77,14 @@ __global__ __launch_bounds__(BR * kBwdLanes) void attn_f32_bwd_dq_kernel(
 #pragma unroll
   for (int i = 0; i < QS; ++i) {
     const int j = part + kBwdLanes * i;
-    qreg[i] = (active && j < kred) ? q[row_off + perm_lds[j * G]] : 0.0f;
+    qreg[i] = (active && j < kred) ? (float)q[row_off + perm_lds[j * G]] : 0.0f;
     dqr[i] = 0.0f;
   }
   float dsum = 0.0f;
 #pragma unroll
   for (int c = 0; c < CS; ++c) {
-    doreg[c] = active ? dout[row_off + part * CS + c] : 0.0f;
-    dsum = __builtin_fmaf(doreg[c], active ? o[row_off + part * CS + c] : 0.0f, dsum);
+    doreg[c] = active ? (float)dout[row_off + part * CS + c] : 0.0f;
+    dsum = __builtin_fmaf(doreg[c], active ? (float)o[row_off + part * CS + c] : 0.0f, dsum);
   }
   const float Drow = quad_sum(dsum);
   const float lse_row = active ? lse[(size_t)bh * N + i_abs] : 0.0f;
@@ -94,8 +95,8 @@ __global__ __launch_bounds__(BR * kBwdLanes) void attn_f32_bwd_dq_kernel(
     __syncthreads();
     for (int i = tid; i < tn * D; i += T) {
       int n = i / D, c = i % D;
-      k_lds[n][c] = kh[(size_t)(n0 + n) * D + c];
-      v_lds[n][c] = vh[(size_t)(n0 + n) * D + c];
+      k_lds[n][c] = (float)kh[(size_t)(n0 + n) * D + c];
+      v_lds[n][c] = (float)vh[(size_t)(n0 + n) * D + c];
     }
     __syncthreads();
     for (int i = tid; i < tn * kred; i += T) {   // fusion, members in sorted order
@@ -127,24 +128,24 @@ __global__ __launch_bounds__(BR * kBwdLanes) void attn_f32_bwd_dq_kernel(
     }
   }
   if (active) {
-    float* dqrow = dq + row_off;
+    E* dqrow = dq + row_off;
     // the row's four lanes write disjoint columns: zeros where the channel was not sampled,
     // the gradient of column j of Q_r at the channel it was sampled from
     for (int c = part; c < D; c += kBwdLanes)
-      if (!sampled_lds[c]) dqrow[c] = 0.0f;
+      if (!sampled_lds[c]) dqrow[c] = (E)0.0f;
 #pragma unroll
     for (int i = 0; i < QS; ++i) {
       const int j = part + kBwdLanes * i;
-      if (j < kred) dqrow[perm_lds[j * G]] = scale * dqr[i];
+      if (j < kred) dqrow[perm_lds[j * G]] = (E)(scale * dqr[i]);
     }
   }
 }
 
-template <int D>
+template <typename E, int D>
 __global__ __launch_bounds__(kBwdTile * kBwdLanes) void attn_f32_bwd_dkv_kernel(
-    const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ v,
-    const float* __restrict__ o, const float* __restrict__ dout, const float* __restrict__ lse,
-    float* __restrict__ dk, float* __restrict__ dv, const uint8_t* __restrict__ perm, int H, int Hkv,
+    const E* __restrict__ q, const E* __restrict__ k, const E* __restrict__ v,
+    const E* __restrict__ o, const E* __restrict__ dout, const float* __restrict__ lse,
+    E* __restrict__ dk, E* __restrict__ dv, const uint8_t* __restrict__ perm, int H, int Hkv,
     int N, int Nk, int Br, int Tq, int Tk, int n_groups, int causal, float scale, int distr) {
   constexpr int T = kBwdTile * kBwdLanes;
   constexpr int QS = D / kBwdLanes;
@@ -171,17 +172,17 @@ __global__ __launch_bounds__(kBwdTile * kBwdLanes) void attn_f32_bwd_dkv_kernel(
   const int G = D / kred;
   const int shift = Nk - N;
 
-  const float* kh = k + ((size_t)bk * Nk + n0) * D;
-  const float* vh = v + ((size_t)bk * Nk + n0) * D;
+  const E* kh = k + ((size_t)bk * Nk + n0) * D;
+  const E* vh = v + ((size_t)bk * Nk + n0) * D;
   for (int i = tid; i < kBwdTile * D; i += T) {
     int n = i / D, c = i % D;
-    k_lds[n][c] = n < tn ? kh[(size_t)n * D + c] : 0.0f;
+    k_lds[n][c] = n < tn ? (float)kh[(size_t)n * D + c] : 0.0f;
     dk_lds[n][c] = 0.0f;
   }
   float vreg[CS], dvacc[CS];
 #pragma unroll
   for (int c = 0; c < CS; ++c) {
-    vreg[c] = valid ? vh[(size_t)key * D + part * CS + c] : 0.0f;
+    vreg[c] = valid ? (float)vh[(size_t)key * D + part * CS + c] : 0.0f;
     dvacc[c] = 0.0f;
   }
   // causal: the first Q block with a row that sees key n0 (row i sees it iff i >= n0 - shift)
@@ -214,8 +215,8 @@ __global__ __launch_bounds__(kBwdTile * kBwdLanes) void attn_f32_bwd_dkv_kernel(
         const size_t base = (bh * N + r0 + c0) * D;
         for (int i = tid; i < cr * D; i += T) {
           int r = i / D, c = i % D;
-          do_lds[r][c] = dout[base + (size_t)r * D + c];
-          if (c < kred) qr_lds[r][c] = q[base + (size_t)r * D + perm_lds[c * G]];
+          do_lds[r][c] = (float)dout[base + (size_t)r * D + c];
+          if (c < kred) qr_lds[r][c] = (float)q[base + (size_t)r * D + perm_lds[c * G]];
         }
         {
           constexpr int TPR = T / kBwdChunk;   // threads per staged row
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(kBwdTile * kBwdLanes) void attn_f32_bwd_dkv_kernel(
           float acc = 0.0f;
           if (r < cr)
             for (int c = sub; c < D; c += TPR)
-              acc = __builtin_fmaf(dout[base + (size_t)r * D + c], o[base + (size_t)r * D + c], acc);
+              acc = __builtin_fmaf((float)dout[base + (size_t)r * D + c], (float)o[base + (size_t)r * D + c], acc);
 #pragma unroll
           for (int m = 1; m < TPR; m <<= 1) acc += __shfl_xor(acc, m);
           if (r < cr && sub == 0) {
@@ -267,30 +268,31 @@ __global__ __launch_bounds__(kBwdTile * kBwdLanes) void attn_f32_bwd_dkv_kernel(
     }
   }
   __syncthreads();
-  float* dkh = dk + ((size_t)bk * Nk + n0) * D;
-  float* dvh = dv + ((size_t)bk * Nk + n0) * D;
+  E* dkh = dk + ((size_t)bk * Nk + n0) * D;
+  E* dvh = dv + ((size_t)bk * Nk + n0) * D;
   for (int i = tid; i < tn * D; i += T) {
     int n = i / D, c = i % D;
-    dkh[(size_t)n * D + c] = scale * dk_lds[n][c];
+    dkh[(size_t)n * D + c] = (E)(scale * dk_lds[n][c]);
   }
   if (valid) {
 #pragma unroll
-    for (int c = 0; c < CS; ++c) dvh[(size_t)key * D + part * CS + c] = dvacc[c];
+    for (int c = 0; c < CS; ++c) dvh[(size_t)key * D + part * CS + c] = (E)dvacc[c];
   }
 }
 
-hipError_t launch_attn_f32_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
-                               const float* lse, void* dq, void* dk, void* dv, const uint8_t* perm,
-                               const Problem& pb, int distr, hipStream_t stream) {
+template <typename T>
+static hipError_t launch_bwd_typed(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                                   const float* lse, void* dq, void* dk, void* dv, const uint8_t* perm,
+                                   const Problem& pb, int distr, hipStream_t stream) {
   const int Tq = (pb.N + pb.Br - 1) / pb.Br;
   const int Tk = (pb.Nk + kBwdTile - 1) / kBwdTile;
   const long long q_units = (long long)pb.B * pb.H * Tq;
   const long long k_units = (long long)pb.B * pb.Hkv * Tk;
   if (k_units > 0x7fffffffLL) return hipErrorInvalidValue;
-#define DA_BWD_DQ(DD, BB)                                                                                    \
-  hipLaunchKernelGGL((attn_f32_bwd_dq_kernel<DD, BB>), dim3((unsigned)q_units), dim3(BB * kBwdLanes), 0, stream, \
-                     (const float*)q, (const float*)k, (const float*)v, (const float*)o, (const float*)dout, \
-                     lse, (float*)dq, perm, pb.H, pb.Hkv, pb.N, pb.Nk, Tq, pb.n_groups, pb.causal, pb.scale, distr)
+#define DA_BWD_DQ(DD, BB)                                                                                       \
+  hipLaunchKernelGGL((attn_f32_bwd_dq_kernel<T, DD, BB>), dim3((unsigned)q_units), dim3(BB * kBwdLanes), 0, stream, \
+                     (const T*)q, (const T*)k, (const T*)v, (const T*)o, (const T*)dout, lse, (T*)dq, perm, pb.H, \
+                     pb.Hkv, pb.N, pb.Nk, Tq, pb.n_groups, pb.causal, pb.scale, distr)
   if (pb.d == 64 && pb.Br == 64) DA_BWD_DQ(64, 64);
   else if (pb.d == 64 && pb.Br == 128) DA_BWD_DQ(64, 128);
   else if (pb.d == 64 && pb.Br == 256) DA_BWD_DQ(64, 256);
@@ -301,15 +303,21 @@ hipError_t launch_attn_f32_bwd(const void* q, const void* k, const void* v, cons
 #undef DA_BWD_DQ
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-#define DA_BWD_DKV(DD)                                                                                         \
-  hipLaunchKernelGGL((attn_f32_bwd_dkv_kernel<DD>), dim3((unsigned)k_units), dim3(kBwdTile * kBwdLanes), 0, stream, \
-                     (const float*)q, (const float*)k, (const float*)v, (const float*)o, (const float*)dout,   \
-                     lse, (float*)dk, (float*)dv, perm, pb.H, pb.Hkv, pb.N, pb.Nk, pb.Br, Tq, Tk, pb.n_groups,  \
-                     pb.causal, pb.scale, distr)
+#define DA_BWD_DKV(DD)                                                                                            \
+  hipLaunchKernelGGL((attn_f32_bwd_dkv_kernel<T, DD>), dim3((unsigned)k_units), dim3(kBwdTile * kBwdLanes), 0, stream, \
+                     (const T*)q, (const T*)k, (const T*)v, (const T*)o, (const T*)dout, lse, (T*)dk, (T*)dv, perm,  \
+                     pb.H, pb.Hkv, pb.N, pb.Nk, pb.Br, Tq, Tk, pb.n_groups, pb.causal, pb.scale, distr)
   if (pb.d == 64) DA_BWD_DKV(64);
   else DA_BWD_DKV(128);
 #undef DA_BWD_DKV
   return hipGetLastError();
+}
+
+hipError_t launch_attn_f32_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                               const float* lse, void* dq, void* dk, void* dv, const uint8_t* perm,
+                               const Problem& pb, int dtype, int distr, hipStream_t stream) {
+  return dtype == 0 ? launch_bwd_typed<bf16>(q, k, v, o, dout, lse, dq, dk, dv, perm, pb, distr, stream)
+                    : launch_bwd_typed<float>(q, k, v, o, dout, lse, dq, dk, dv, perm, pb, distr, stream);
 }
 
 }  // namespace da

@@ -86,10 +86,11 @@ hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, void* o
 hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
                            const Problem& pb, int distr, hipStream_t stream);
 bool attn_bf16_supported(const Problem& pb, int distr);
-// Float backward: dq [B][H][N][d], dk and dv [B][Hkv][Nk][d] from the forward's inputs, its output
+// Backward in float arithmetic (tensors bf16 or float by dtype): dq [B][H][N][d], dk and dv
+// [B][Hkv][Nk][d] from the forward's inputs, its output
 // o, the output gradient dout and the forward's row statistics lse; perm as in launch_attn_f32.
 hipError_t launch_attn_f32_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
                                const float* lse, void* dq, void* dk, void* dv, const uint8_t* perm,
-                               const Problem& pb, int distr, hipStream_t stream);
+                               const Problem& pb, int dtype, int distr, hipStream_t stream);
 
 }  // namespace da
