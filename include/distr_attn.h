@@ -90,7 +90,8 @@ typedef struct {
   int side;             /* 0: sample Q columns, fuse K columns, one grouping per Q block (Sec. 3.2-3.3,
                            the form the paper builds). 1: the mirrored form of Sec. 3.1 / Fig. 4 right:
                            sample K columns, fuse Q columns, one grouping per K block of Bc rows taken
-                           from that K block; float only, Bc in {32, 64, 128}; perm_in / perm_out /
+                           from that K block; Bc in {32, 64, 128}; float arithmetic on the vector ALUs
+                           for both dtypes (bf16 tensors are converted on load); perm_in / perm_out /
                            hash_out are then [B][Hkv][Tk][d]                                        */
   float *lse_out;       /* optional device [B][H][N] float: natural logarithm of the sum over the visible
                            keys of exp(score) of every query row -- the row statistics of the softmax

@@ -84,7 +84,6 @@ int resolve(const da_params* p, bool need_groups, Resolved* out) {
     return fail(DA_ERR_UNSUPPORTED, "Br = %d: kernels are built for Br in {64, 128, 256}", p->Br);
   const bool mirrored = need_groups && p->side == 1;
   if (mirrored) {
-    if (p->dtype != DA_F32) return fail(DA_ERR_UNSUPPORTED, "side = 1 (sample K, fuse Q) is built for the float path only");
     if (p->Bc != 32 && p->Bc != 64 && p->Bc != 128)
       return fail(DA_ERR_UNSUPPORTED, "Bc = %d: side = 1 groups K blocks of 32, 64 or 128 rows", p->Bc);
   } else if (p->Bc != 32 && p->Bc != 64 && p->Bc != 128) {
@@ -136,6 +135,10 @@ size_t kt_bytes(const Resolved& r) {
   return da::kt_copy_bytes(r.pb.B, r.pb.Hkv, r.pb.d, r.pb.Nk) + da::kRtabBytes;
 }
 
+// The transposed copy of K is read by the bf16 matrix-core kernels (the mirrored form runs on the
+// float-arithmetic kernel and needs none).
+bool needs_kt(const Resolved& r) { return r.dtype == DA_BF16 && r.pb.side == 0; }
+
 // Address of the static scratch array on the current device (looked up once per device).
 int static_scratch(void** out) {
   int dev = 0;
@@ -156,7 +159,7 @@ int static_scratch(void** out) {
 // table when the grouping comes from perm_in, goes to perm_out, or stays inside the attention
 // kernel. Source: the caller's workspace, the static array (no_alloc), or the library-owned buffer.
 int get_scratch(const da_params* p, const Resolved& r, bool need_table, bool no_alloc, uint8_t** perm, void** kt) {
-  const size_t kt_need = (r.dtype == DA_BF16 && !p->kt_in) ? kt_bytes(r) : 0;
+  const size_t kt_need = (needs_kt(r) && !p->kt_in) ? kt_bytes(r) : 0;
   const size_t perm_need = need_table ? perm_bytes(r) : 0;
   const size_t need = kt_need + perm_need;
   char* base = nullptr;
@@ -229,7 +232,7 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
   if (rc) return rc;
   rc = check_tensors(q, k, v, o);
   if (rc) return rc;
-  if (r.dtype == DA_BF16 && !da::attn_bf16_supported(r.pb, distr ? 1 : 0))
+  if (r.dtype == DA_BF16 && r.pb.side == 0 && !da::attn_bf16_supported(r.pb, distr ? 1 : 0))
     return fail(DA_ERR_UNSUPPORTED, "bf16 kernels need n_groups in {4, 8, 16, 32, 64, 128} (16, 32, 64 or d when Bc is not "
                 "64) and groups of at most 16 channels; got d=%d Br=%d Bc=%d n_groups=%d", p->d, p->Br, p->Bc, p->n_groups);
   const uint8_t* perm = nullptr;
@@ -237,7 +240,7 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
   // Groups of one channel (G* = 1): S^ = Q_r K_f^T is Q K^T with its terms taken in the sorted
   // channel order (Sec. 3.1: one column per group reproduces S). The bf16 path then runs the
   // exact kernel; the LSH stage still runs if the caller asked for its tables.
-  const bool trivial_groups = distr && r.dtype == DA_BF16 && p->n_groups == p->d;
+  const bool trivial_groups = distr && r.dtype == DA_BF16 && r.pb.side == 0 && p->n_groups == p->d;
   if (trivial_groups) {
     if (!p->perm_in && (p->perm_out || p->hash_out)) {
       rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, p->perm_out, p->hash_out, r.stream), "lsh_group launch", r.stream);
@@ -248,7 +251,7 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
   if (distr) {
     // bf16 path, up to 16 projections, no table asked for: the attention kernel hashes and groups
     // its own Q block in its prologue (same arithmetic as the LSH kernel) and no table is written.
-    const bool lsh_in_kernel = r.dtype == DA_BF16 && !p->perm_in && !p->perm_out && !p->hash_out && r.pb.n_planes <= 16;
+    const bool lsh_in_kernel = r.dtype == DA_BF16 && r.pb.side == 0 && !p->perm_in && !p->perm_out && !p->hash_out && r.pb.n_planes <= 16;
     const bool run_lsh = !p->perm_in && !lsh_in_kernel;
     uint8_t* table = nullptr;
     rc = get_scratch(p, r, run_lsh && !p->perm_out, no_alloc, &table, &kt);
@@ -264,17 +267,18 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
       if (rc) return rc;
       perm = table;
     }
-    if (r.dtype == DA_BF16 && p->kt_in) {
+    if (needs_kt(r) && p->kt_in) {
       if (((uintptr_t)p->kt_in & 255u) != 0) return fail(DA_ERR_INVALID_ARG, "kt_in must be 256-byte aligned");
       kt = const_cast<void*>(p->kt_in);
-    } else if (r.dtype == DA_BF16) {
+    } else if (needs_kt(r)) {
       rc = check_launch(da::launch_kt_prepass(k, kt, r.pb, r.stream), "key pre-pass launch", r.stream);
       if (rc) return rc;
     }
   }
-  hipError_t e = (r.dtype == DA_BF16)
+  // (the mirrored form runs on the float-arithmetic kernel for either dtype)
+  hipError_t e = (r.dtype == DA_BF16 && !(distr && r.pb.side == 1))
                      ? da::launch_attn_bf16(q, k, v, o, perm, kt, r.pb, distr ? 1 : 0, r.stream)
-                     : da::launch_attn_f32(q, k, v, o, perm, r.pb, distr ? 1 : 0, r.stream);
+                     : da::launch_attn_f32(q, k, v, o, perm, r.pb, r.dtype, distr ? 1 : 0, r.stream);
   return check_launch(e, "attention launch", r.stream);
 }
 
@@ -394,7 +398,7 @@ size_t distr_attn_kt_bytes(const da_params* p) {
 size_t distr_attn_workspace_bytes(const da_params* p) {
   Resolved r;
   if (resolve(p, true, &r)) return 0;
-  return kt_bytes(r) + perm_bytes(r);
+  return (needs_kt(r) ? kt_bytes(r) : 0) + perm_bytes(r);
 }
 
 int distr_attn_hyperplanes(uint64_t seed, int n_planes, int Br, float* host_out) {

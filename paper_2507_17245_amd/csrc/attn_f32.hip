@@ -1,4 +1,5 @@
-// Float attention forward (exact and DistrAttention) for gfx950: the reference-precision path.
+// Attention forward (exact and DistrAttention) in float arithmetic for gfx950: the reference-precision
+// path, for float tensors and (the mirrored form only) for bf16 tensors converted on load.
 //
 // Same steps as the bf16 kernel (Sec. 2.2.2 tiling; Sec. 3.2 sampling and fusion per Q block,
 // Sec. 3.3; Eq. 2), in plain float FMAs on the vector ALUs. Four adjacent lanes share one query
@@ -20,10 +21,10 @@ namespace da {
 constexpr int kF32Tile = 32;  // key rows per LDS tile of this kernel
 constexpr int kF32Lanes = 4;  // lanes per query row
 
-template <int D, int BR>
+template <typename E, int D, int BR>
 __global__ __launch_bounds__(BR * kF32Lanes) void attn_f32_kernel(
-    const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ v,
-    float* __restrict__ o, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Nk, int Tq,
+    const E* __restrict__ q, const E* __restrict__ k, const E* __restrict__ v,
+    E* __restrict__ o, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Nk, int Tq,
     int n_groups, int causal, float scale, int distr, int side, int Bc, float* __restrict__ lse) {
   constexpr int T = BR * kF32Lanes;
   constexpr int QS = D / kF32Lanes;            // most channels of the score product one lane takes
@@ -45,9 +46,9 @@ __global__ __launch_bounds__(BR * kF32Lanes) void attn_f32_kernel(
   const int kred = distr ? n_groups : D;
   const int G = D / kred;
 
-  const float* qh = q + ((size_t)bh * N + r0) * D;
-  const float* kh = k + ((size_t)(b * Hkv + hk) * Nk) * D;
-  const float* vh = v + ((size_t)(b * Hkv + hk) * Nk) * D;
+  const E* qh = q + ((size_t)bh * N + r0) * D;
+  const E* kh = k + ((size_t)(b * Hkv + hk) * Nk) * D;
+  const E* vh = v + ((size_t)(b * Hkv + hk) * Nk) * D;
   const int shift = Nk - N;   // causal: key n is visible to query i iff n <= i + shift
   const bool mirrored = distr && side == 1;
   const int Tk = (Nk + Bc - 1) / Bc;
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(BR * kF32Lanes) void attn_f32_kernel(
 #pragma unroll
   for (int i = 0; i < QS; ++i) {
     const int j = part + kF32Lanes * i;
-    qreg[i] = (active && j < kred && !mirrored) ? qh[(size_t)row * D + (distr ? perm_lds[j * G] : j)] : 0.0f;
+    qreg[i] = (active && j < kred && !mirrored) ? (float)qh[(size_t)row * D + (distr ? perm_lds[j * G] : j)] : 0.0f;
   }
 
   float acc[CS];
@@ -86,14 +87,14 @@ __global__ __launch_bounds__(BR * kF32Lanes) void attn_f32_kernel(
         const int j = part + kF32Lanes * i;
         float s = 0.0f;
         if (active && j < kred)
-          for (int g = 0; g < G; ++g) s += qh[(size_t)row * D + perm_lds[j * G + g]];
+          for (int g = 0; g < G; ++g) s += (float)qh[(size_t)row * D + perm_lds[j * G + g]];
         qreg[i] = s;
       }
     }
     for (int i = tid; i < tn * D; i += T) {
       int n = i / D, c = i % D;
-      k_lds[n][c] = kh[(size_t)(n0 + n) * D + c];
-      v_lds[n][c] = vh[(size_t)(n0 + n) * D + c];
+      k_lds[n][c] = (float)kh[(size_t)(n0 + n) * D + c];
+      v_lds[n][c] = (float)vh[(size_t)(n0 + n) * D + c];
     }
     __syncthreads();
     if (mirrored) {  // sampling on the K side: the group's first channel in sorted order
@@ -158,21 +159,22 @@ __global__ __launch_bounds__(BR * kF32Lanes) void attn_f32_kernel(
   if (active) {
     if (lse && part == 0) lse[(size_t)bh * N + i_abs] = m_run + logf(l_run);   // row statistics for a backward pass
     float inv = 1.0f / l_run;
-    float* orow = o + ((size_t)bh * N + i_abs) * D + part * CS;
+    E* orow = o + ((size_t)bh * N + i_abs) * D + part * CS;
 #pragma unroll
-    for (int c = 0; c < CS; ++c) orow[c] = acc[c] * inv;
+    for (int c = 0; c < CS; ++c) orow[c] = (E)(acc[c] * inv);
   }
 }
 
-hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
-                           const Problem& pb, int distr, hipStream_t stream) {
+template <typename E>
+static hipError_t launch_f32_typed(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
+                                   const Problem& pb, int distr, hipStream_t stream) {
   const int Tq = (pb.N + pb.Br - 1) / pb.Br;
   const long long units = (long long)pb.B * pb.H * Tq;
   dim3 grid((unsigned)units);
-#define DA_F32_LAUNCH(DD, BB)                                                                      \
-  hipLaunchKernelGGL((attn_f32_kernel<DD, BB>), grid, dim3(BB * kF32Lanes), 0, stream, (const float*)q,        \
-                     (const float*)k, (const float*)v, (float*)o, perm, pb.H, pb.Hkv, pb.N, pb.Nk, Tq, \
-                     pb.n_groups, pb.causal, pb.scale, distr, pb.side, pb.Bc, pb.lse)
+#define DA_F32_LAUNCH(DD, BB)                                                                          \
+  hipLaunchKernelGGL((attn_f32_kernel<E, DD, BB>), grid, dim3(BB * kF32Lanes), 0, stream, (const E*)q,  \
+                     (const E*)k, (const E*)v, (E*)o, perm, pb.H, pb.Hkv, pb.N, pb.Nk, Tq, pb.n_groups, \
+                     pb.causal, pb.scale, distr, pb.side, pb.Bc, pb.lse)
   if (pb.d == 64 && pb.Br == 64) DA_F32_LAUNCH(64, 64);
   else if (pb.d == 64 && pb.Br == 128) DA_F32_LAUNCH(64, 128);
   else if (pb.d == 128 && pb.Br == 64) DA_F32_LAUNCH(128, 64);
@@ -182,6 +184,13 @@ hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o,
   else return hipErrorInvalidValue;
 #undef DA_F32_LAUNCH
   return hipGetLastError();
+}
+
+// dtype 0: bf16 tensors (converted on load, rounded on store), 1: float tensors; float arithmetic either way
+hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
+                           const Problem& pb, int dtype, int distr, hipStream_t stream) {
+  return dtype == 0 ? launch_f32_typed<bf16>(q, k, v, o, perm, pb, distr, stream)
+                    : launch_f32_typed<float>(q, k, v, o, perm, pb, distr, stream);
 }
 
 }  // namespace da

@@ -84,7 +84,7 @@ hipError_t launch_kt_prepass(const void* k, void* kt, const Problem& pb, hipStre
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
                             const void* kt, const Problem& pb, int distr, hipStream_t stream);
 hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
-                           const Problem& pb, int distr, hipStream_t stream);
+                           const Problem& pb, int dtype, int distr, hipStream_t stream);
 bool attn_bf16_supported(const Problem& pb, int distr);
 // Backward in float arithmetic (tensors bf16 or float by dtype): dq [B][H][N][d], dk and dv
 // [B][Hkv][Nk][d] from the forward's inputs, its output

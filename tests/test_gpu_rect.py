@@ -96,11 +96,21 @@ def test_mirrored_form(Nq, Nk, causal, Bc):
         U.assert_close(o_t, oracle.distr_fwd(q, k, v, p, perm=table), "f32", "mirrored, caller's table")
 
 
-def test_mirrored_form_is_refused_for_bf16():
-    import torch
-    import paper_2507_17245_amd as da
-    q = torch.zeros((1, 2, 64, 64), dtype=torch.bfloat16, device="cuda")
-    o = torch.empty_like(q)
-    with pytest.raises(da.DistrAttnError) as e:
-        da.distr_attn_fwd_ex(q, q, q, o, da.make_params(q, q, q, Br=64, n_groups=32, side=1))
-    assert e.value.code == da.DA_ERR_UNSUPPORTED
+@pytest.mark.parametrize("Nq,Nk,causal,Bc", [(256, 256, False, 64), (100, 333, True, 32), (200, 200, True, 128)])
+def test_mirrored_form_on_bf16_tensors(Nq, Nk, causal, Bc):
+    """side = 1 with bf16 tensors runs the float-arithmetic kernel (values converted on load, the
+    output rounded on store): the K blocks' tables bit for bit, the output within the bf16 bar."""
+    import gpu_util as U
+    for d, Br, ng in ((64, 64, 32), (128, 128, 32), (128, 64, 64)):
+        cfg = small("vit", B=2, H=4, Hkv=2, N=Nq, Nk=Nk, causal=causal, d=d, Br=Br, Bc=Bc, n_groups=ng,
+                    side=1, n_planes=16)
+        assert cfg.dtype == "bf16"
+        q, k, v = W.make(cfg)
+        p = U.oracle_params(cfg)
+        print(f"case {cfg}", flush=True)
+        o_gpu, perm_gpu, hash_gpu = U.run_gpu(cfg, q, k, v, distr=True, want_tables=True)
+        hash_ref, perm_ref = U.oracle_tables(cfg, q, k)
+        assert np.array_equal(hash_gpu, hash_ref) and np.array_equal(perm_gpu, perm_ref)
+        U.assert_close(o_gpu, oracle.distr_fwd(q, k, v, p), "bf16", "mirrored, bf16 tensors")
+        o_ws, _, _ = U.run_gpu(cfg, q, k, v, distr=True)      # table in the library's workspace
+        assert np.array_equal(o_ws, o_gpu)

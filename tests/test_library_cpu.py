@@ -72,7 +72,7 @@ FAKE_O = ctypes.c_void_p(0x2000)
     (dict(Bc=96), da.DA_ERR_UNSUPPORTED),
     (dict(Br=512), da.DA_ERR_UNSUPPORTED),
     (dict(Bc=32, n_groups=8), da.DA_ERR_UNSUPPORTED),     # tiles other than 64 rows: 16, 32, 64 groups or d
-    (dict(side=1), da.DA_ERR_UNSUPPORTED),                # the mirrored form is float only
+    (dict(side=1, Bc=96), da.DA_ERR_UNSUPPORTED),         # the mirrored form: K blocks of 32, 64 or 128 rows
     (dict(side=2), da.DA_ERR_INVALID_ARG),
     (dict(Nk=50, causal=1), da.DA_ERR_INVALID_ARG),       # causal with fewer keys than queries
     (dict(Nk=-1), da.DA_ERR_INVALID_ARG),
