@@ -120,21 +120,24 @@ int distr_attn_fwd_ex(const void *q, const void *k, const void *v, void *o, cons
 int distr_attn_exact_fwd_ex(const void *q, const void *k, const void *v, void *o, const da_params *p);
 
 /*
- * Backward pass of the two calls above (side = 0), in float arithmetic on the vector ALUs for both
- * dtypes: float tensors, or bf16 tensors converted on load and rounded on store (a
- * reference-speed path; there is no matrix-core backward). The paper
- * trains through the method (Sec. 4.3, 4.4) without giving a gradient; computed here is the
- * derivative of the forward with every query block's grouping held fixed (the grouping is a
- * piecewise-constant function of q): with P = softmax(S^), dP = dout V^T, D_i = sum_c dout_ic o_ic
- * and dS^ = P o (dP - D),  dv = P^T dout;  dq[:, first channel of group j] = scale (dS^ K_f)[:, j]
- * and 0 in the block's other columns;  dk[:, c] = scale * sum over query blocks of
- * (dS^T Q_r)[:, group of c in that block]  (Q_r, K_f: sampled and fused columns, Sec. 3.2, Eq. 2).
- * The exact call is the case of one channel per group (Sec. 2.1).
+ * Backward pass of the two calls above (side = 0). The paper trains through the method (Sec. 4.3,
+ * 4.4) without giving a gradient; computed here is the derivative of the forward with every query
+ * block's grouping held fixed (the grouping is a piecewise-constant function of q): with
+ * P = softmax(S^), dP = dout V^T, D_i = sum_c dout_ic o_ic and dS^ = P o (dP - D),
+ * dv = P^T dout;  dq[:, first channel of group j] = scale (dS^ K_f)[:, j] and 0 in the block's
+ * other columns;  dk[:, c] = scale * sum over query blocks of (dS^T Q_r)[:, group of c in that
+ * block]  (Q_r, K_f: sampled and fused columns, Sec. 3.2, Eq. 2). The exact call is the case of
+ * one channel per group (Sec. 2.1).
+ * bf16 tensors: matrix-core kernels (bf16 operands, fp32 accumulate; P and dS^ are rounded to bf16
+ * before the products that take them), d in {64, 128}, any n_groups that divides d. float tensors:
+ * float arithmetic on the vector ALUs (a reference-precision path).
  * q, k, v, p: as given to the forward; o: its output; lse: its lse_out; dout [B][H][N][d]: gradient
  * of the loss with respect to o, same dtype. Written: dq [B][H][N][d], dk and dv [B][Hkv][Nk][d]
  * (p->dtype, device, 16-byte aligned, distinct from every input and from each other). The grouping is recomputed
- * from q (same seed and options give the forward's table) unless p->perm_in brings it; the table
- * lives in the workspace as in the forward. No atomics: results are the same on every run.
+ * from q (same seed and options give the forward's table) unless p->perm_in brings it. Scratch
+ * (the table, and for bf16 tensors D and a copy of q, see distr_attn_bwd_workspace_bytes) comes
+ * from p->workspace, else from the library-owned buffer as in the forward. No atomics: results
+ * are the same on every run.
  * Errors: as the forward; DA_ERR_UNSUPPORTED for side = 1.
  */
 int distr_attn_bwd_ex(const void *q, const void *k, const void *v, const void *o, const void *dout,
@@ -142,6 +145,10 @@ int distr_attn_bwd_ex(const void *q, const void *k, const void *v, const void *o
 int distr_attn_exact_bwd_ex(const void *q, const void *k, const void *v, const void *o,
                             const void *dout, const float *lse, void *dq, void *dk, void *dv,
                             const da_params *p);
+
+/* Bytes of p->workspace the backward calls need at most for p (0 for invalid parameters):
+ * the grouping table and, for bf16 tensors, 4 bytes per query row plus a copy of q. */
+size_t distr_attn_bwd_workspace_bytes(const da_params *p);
 
 /*
  * LSH hash-and-group stage alone (Sec. 3.2 "similar columns identification", Fig. 5): writes

@@ -19,7 +19,7 @@ EXPORTS = (
     "distr_attn_fwd_noalloc", "distr_attn_noalloc_max_bytes",
     "distr_attn_bwd_ex", "distr_attn_exact_bwd_ex",
     "distr_attn_lsh_group", "distr_attn_key_prepass", "distr_attn_kt_bytes",
-    "distr_attn_workspace_bytes", "distr_attn_hyperplanes",
+    "distr_attn_workspace_bytes", "distr_attn_bwd_workspace_bytes", "distr_attn_hyperplanes",
     "distr_attn_set_stream", "distr_attn_release", "distr_attn_last_error", "distr_attn_version",
 )
 
@@ -64,7 +64,7 @@ def lib():
             getattr(L, name).argtypes = [vp] * 9 + [ctypes.POINTER(DaParams)]
         L.distr_attn_lsh_group.argtypes = [vp, ctypes.POINTER(DaParams)]
         L.distr_attn_key_prepass.argtypes = [vp, vp, ctypes.POINTER(DaParams)]
-        for name in ("distr_attn_workspace_bytes", "distr_attn_kt_bytes"):
+        for name in ("distr_attn_workspace_bytes", "distr_attn_bwd_workspace_bytes", "distr_attn_kt_bytes"):
             getattr(L, name).argtypes = [ctypes.POINTER(DaParams)]
             getattr(L, name).restype = ctypes.c_size_t
         L.distr_attn_hyperplanes.argtypes = [u64, ci, ci, ctypes.POINTER(ctypes.c_float)]
@@ -278,6 +278,10 @@ def distr_attn_kt_bytes(params):
 
 def distr_attn_workspace_bytes(params):
     return int(lib().distr_attn_workspace_bytes(ctypes.byref(params)))
+
+
+def distr_attn_bwd_workspace_bytes(params):
+    return int(lib().distr_attn_bwd_workspace_bytes(ctypes.byref(params)))
 
 
 def distr_attn_hyperplanes(seed, n_planes, Br):

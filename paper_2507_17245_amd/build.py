@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libdistr_attn.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["attn_bf16_bc64.hip", "attn_bf16_bc128.hip", "attn_bf16_bc32.hip", "api.hip", "lsh_group.hip",
-           "kt_prepass.hip", "attn_bf16.hip", "attn_f32.hip", "attn_f32_bwd.hip"]
+           "kt_prepass.hip", "attn_bf16.hip", "attn_f32.hip", "attn_f32_bwd.hip", "attn_bf16_bwd.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          # packed-fp32 VALU forms are switched off for every kernel of this library

@@ -158,16 +158,8 @@ int static_scratch(void** out) {
 // writes are asked for: no K^T copy when the caller brings kt_in (or on the float path), no
 // table when the grouping comes from perm_in, goes to perm_out, or stays inside the attention
 // kernel. Source: the caller's workspace, the static array (no_alloc), or the library-owned buffer.
-int get_scratch(const da_params* p, const Resolved& r, bool need_table, bool no_alloc, uint8_t** perm, void** kt) {
-  const size_t kt_need = (needs_kt(r) && !p->kt_in) ? kt_bytes(r) : 0;
-  const size_t perm_need = need_table ? perm_bytes(r) : 0;
-  const size_t need = kt_need + perm_need;
+int scratch_base(const da_params* p, const Resolved& r, size_t need, bool no_alloc, char** out) {
   char* base = nullptr;
-  if (need == 0) {
-    *kt = nullptr;
-    *perm = nullptr;
-    return DA_OK;
-  }
   if (no_alloc) {
     if (need > kStaticScratchBytes)
       return fail(DA_ERR_WORKSPACE, "distr_attn_fwd_noalloc: %zu bytes of scratch needed, the static array holds %zu "
@@ -200,9 +192,31 @@ int get_scratch(const da_params* p, const Resolved& r, bool need_table, bool no_
     }
     base = (char*)g_ws_ptr[dev];
   }
+  *out = base;
+  return DA_OK;
+}
+
+int get_scratch(const da_params* p, const Resolved& r, bool need_table, bool no_alloc, uint8_t** perm, void** kt) {
+  const size_t kt_need = (needs_kt(r) && !p->kt_in) ? kt_bytes(r) : 0;
+  const size_t perm_need = need_table ? perm_bytes(r) : 0;
+  const size_t need = kt_need + perm_need;
+  char* base = nullptr;
+  if (need == 0) {
+    *kt = nullptr;
+    *perm = nullptr;
+    return DA_OK;
+  }
+  int rc = scratch_base(p, r, need, no_alloc, &base);
+  if (rc) return rc;
   *kt = kt_need ? (void*)base : nullptr;
   *perm = perm_need ? (uint8_t*)(base + kt_need) : nullptr;
   return DA_OK;
+}
+
+// Scratch of the backward pass: [permutation table, when the LSH stage runs and the table is not
+// exported | what the bf16 kernels keep between their launches (D_i, Q~)].
+size_t bwd_tail_bytes(const Resolved& r, bool distr) {
+  return r.dtype == DA_BF16 ? da::attn_bf16_bwd_scratch_bytes(r.pb, distr ? 1 : 0) : 0;
 }
 
 // DISTR_ATTN_DEBUG=1 in the environment (read once): wait for the device after every launch, so
@@ -300,22 +314,30 @@ int attention_bwd(const void* q, const void* k, const void* v, const void* o, co
       if (x == y) return fail(DA_ERR_INVALID_ARG, "dq, dk, dv must not alias an input");
   }
   if (dq == dk || dq == dv || dk == dv) return fail(DA_ERR_INVALID_ARG, "dq, dk, dv must be distinct buffers");
+  const bool own_table = distr && !p->perm_in && !p->perm_out;
+  const size_t table_need = own_table ? perm_bytes(r) : 0;
+  const size_t tail_need = bwd_tail_bytes(r, distr);
+  char* base = nullptr;
+  if (table_need + tail_need) {
+    rc = scratch_base(p, r, table_need + tail_need, false, &base);
+    if (rc) return rc;
+  }
   const uint8_t* perm = nullptr;
   if (distr) {
     if (p->perm_in) {
       perm = p->perm_in;
     } else {
-      uint8_t* table = nullptr;
-      void* kt = nullptr;
-      rc = get_scratch(p, r, !p->perm_out, false, &table, &kt);
-      if (rc) return rc;
-      if (p->perm_out) table = p->perm_out;
+      uint8_t* table = p->perm_out ? p->perm_out : (uint8_t*)base;
       rc = check_launch(da::launch_lsh_group(q, r.dtype, r.pb, table, p->hash_out, r.stream), "lsh_group launch", r.stream);
       if (rc) return rc;
       perm = table;
     }
   }
-  return check_launch(da::launch_attn_f32_bwd(q, k, v, o, dout, lse, dq, dk, dv, perm, r.pb, r.dtype, distr ? 1 : 0, r.stream),
+  if (r.dtype == DA_BF16)
+    return check_launch(da::launch_attn_bf16_bwd(q, k, v, o, dout, lse, dq, dk, dv, perm, base + table_need, r.pb,
+                                                 distr ? 1 : 0, r.stream),
+                        "backward launch (matrix cores)", r.stream);
+  return check_launch(da::launch_attn_f32_bwd(q, k, v, o, dout, lse, dq, dk, dv, perm, r.pb, distr ? 1 : 0, r.stream),
                       "backward launch", r.stream);
 }
 
@@ -399,6 +421,12 @@ size_t distr_attn_workspace_bytes(const da_params* p) {
   Resolved r;
   if (resolve(p, true, &r)) return 0;
   return (needs_kt(r) ? kt_bytes(r) : 0) + perm_bytes(r);
+}
+
+size_t distr_attn_bwd_workspace_bytes(const da_params* p) {
+  Resolved r;
+  if (resolve(p, true, &r)) return 0;
+  return perm_bytes(r) + bwd_tail_bytes(r, true);
 }
 
 int distr_attn_hyperplanes(uint64_t seed, int n_planes, int Br, float* host_out) {

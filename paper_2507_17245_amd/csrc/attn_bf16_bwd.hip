@@ -1,0 +1,445 @@
+// Backward of the attention forward (exact and DistrAttention) for bf16 tensors on the gfx950
+// matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate). Three kernels, no atomics (results do
+// not depend on the run).
+//
+// The paper trains through the approximation (Sec. 4.3, 4.4) and gives no gradient; computed here
+// is the derivative of the forward with every Q block's grouping held fixed. With Q_r the sampled
+// and K_f the fused columns of Sec. 3.2 (Eq. 2: S^ = Q_r K_f^T, one grouping per Q block,
+// Sec. 3.3), write Q~ for Q with every channel replaced by its group's sampled channel:
+//   S^ = Q_r K_f^T = Q~ K^T                       (a sum over groups of sums over members)
+//   dK = scale * dS^T Q~                          (every member of a group receives dK_f's column)
+//   dQ[:, sampled channel of group j] = scale * sum over the group's members c of (dS K)[:, c]
+// so the backward of DistrAttention is the backward of exact attention taken on Q~, followed by a
+// sum over each group's members for dQ. P = exp(S^ - lse) is rebuilt from the forward's row
+// statistics, dP = dO V^T, D_i = sum_c dO_ic O_ic, dS = P o (dP - D), dV = P^T dO.
+//
+//   bwd_prepare_kernel  D_i for every row; Q~ (DistrAttention only) into scratch
+//   bwd_dq_kernel       one workgroup per 128 query rows, lane = query row; K and V tiles of 64
+//                       rows stream through LDS:  S^T = K Q~^T, dP^T = V dO^T, dQ~^T += K^T dS^T
+//   bwd_dkv_kernel      one workgroup per 128 keys of a kv head, lane = key; Q~ and dO tiles of 64
+//                       rows of every query head of the group stream through LDS:
+//                       S = Q~ K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q~^T dS
+// In both, the accumulator layout of the first products (registers = streamed rows, lanes =
+// resident rows) is the B-operand layout of the last ones, so P and dS never leave registers; the
+// streamed tiles are read once row-wise (16-byte reads) and once with transposing reads.
+#include "da_common.h"
+
+namespace da {
+
+namespace {
+
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+constexpr int kBwdRows = 128;      // resident rows per workgroup (4 waves x 32)
+constexpr int kBwdStream = 64;     // streamed rows per LDS tile
+constexpr int kBwdThreads = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Position of a 16-byte chunk inside its row of a streamed tile (rows of D bf16, unpadded). A
+// tile is read two ways: 16 lanes take the same chunk of 16 consecutive rows (16-byte reads), and
+// the transposing reads take, per 32 lanes, 64 consecutive bytes of 4 consecutive rows. Both are
+// free of bank conflicts when the chunk index is XORed with these bits of the row.
+template <int D>
+__device__ inline int chunk_swz(int row) {
+  if constexpr (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+  else return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+}
+
+template <int D>
+__device__ inline char* chunk_addr(char* tile, int row, int chunk) {
+  return tile + row * (D * 2) + ((chunk ^ chunk_swz<D>(row)) << 4);
+}
+
+// rows [row0, row0 + 64) of a row-major [n_rows][D] bf16 matrix into an LDS tile, zeros past the end
+template <int D>
+__device__ inline void stage_tile(char* tile, const bf16* __restrict__ src, int row0, int n_rows, int tid) {
+  constexpr int CH = D / 8;
+#pragma unroll
+  for (int it = 0; it < kBwdStream * CH / kBwdThreads; ++it) {
+    const int id = tid + it * kBwdThreads;
+    const int row = id / CH, chunk = id % CH;
+    u32x4 x = {0u, 0u, 0u, 0u};
+    if (row0 + row < n_rows) x = *(const u32x4*)(src + (size_t)(row0 + row) * D + chunk * 8);
+    *(u32x4*)chunk_addr<D>(tile, row, chunk) = x;
+  }
+}
+
+// A operand, row-wise: row `row` of the tile, contraction slots 8*hh .. 8*hh+7 of step s
+template <int D>
+__device__ inline bf16x8 read_rows(char* tile, int row, int s, int hh) {
+  return *(const bf16x8*)chunk_addr<D>(tile, row, 2 * s + hh);
+}
+
+// A operand of a product that contracts over the tile's rows (the tile transposed): output rows
+// are the channels 32*cb + lane%32, the contraction runs over the 16 tile rows from rb on, in the
+// order an accumulator enumerates them (slot j of lane half hh = row 8*(j/4) + 4*hh + j%4).
+// Two ds_read_b64_tr_b16: within 16 lanes, lane i receives element i%4 of the 8-byte pieces
+// addressed by lanes 4j + i/4, j = 0..3.
+template <int D>
+__device__ inline bf16x8 read_transposed(char* tile, int rb, int cb, int lane) {
+  const int hh = lane >> 5;
+  const int row = rb + 4 * hh + ((lane & 15) >> 2);
+  const int chunk = 4 * cb + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+  const int inb = 8 * (lane & 1);
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(chunk_addr<D>(tile, row, chunk) + inb));
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(chunk_addr<D>(tile, row + 8, chunk) + inb));
+  s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// tile row that register i of a 32 x 32 accumulator block holds, for lane half hh
+__device__ inline int acc_row(int i, int hh) { return 8 * (i >> 2) + 4 * hh + (i & 3); }
+
+__device__ inline void zero(f32x16& x) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) x[i] = 0.0f;
+}
+
+// ------------------------------------------------------------------------------------------------
+// D_i = sum_c dO_ic O_ic for every query row; for DistrAttention also Q~: channel c of a row takes
+// the value of the first channel (sorted order) of c's group in the row's Q block.
+template <int D>
+__global__ __launch_bounds__(kBwdThreads) void bwd_prepare_kernel(
+    const bf16* __restrict__ q, const bf16* __restrict__ o, const bf16* __restrict__ dout,
+    const uint8_t* __restrict__ perm, bf16* __restrict__ qrep, float* __restrict__ delta, int N, int Br, int Tq,
+    int n_groups) {
+  constexpr int CH = D / 8;
+  constexpr int RPP = kBwdThreads / CH;   // rows per pass
+  __shared__ uint8_t rep_lds[D];
+  __shared__ __attribute__((aligned(16))) bf16 row_lds[RPP][D];
+  const int tid = threadIdx.x;
+  const int t = blockIdx.x % Tq;
+  const size_t bh = blockIdx.x / Tq;
+  const int r0 = t * Br;
+  const int rows = min(Br, N - r0);
+  if (perm) {
+    const int G = D / n_groups;
+    for (int i = tid; i < D; i += kBwdThreads) {
+      const uint8_t* pr = perm + (size_t)blockIdx.x * D;
+      rep_lds[pr[i] & (D - 1)] = pr[i / G * G] & (D - 1);
+    }
+  }
+  const int rr = tid / CH, chunk = tid % CH;
+  for (int p0 = 0; p0 < rows; p0 += RPP) {
+    const int row = p0 + rr;
+    const bool on = row < rows;
+    const size_t off = ((bh * N) + r0 + (on ? row : 0)) * D + chunk * 8;
+    float acc = 0.0f;
+    if (on) {
+      const bf16x8 a = *(const bf16x8*)(dout + off), b = *(const bf16x8*)(o + off);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc = __builtin_fmaf((float)a[j], (float)b[j], acc);
+    }
+#pragma unroll
+    for (int m = 1; m < CH; m <<= 1) acc += __shfl_xor(acc, m);
+    if (on && chunk == 0) delta[bh * N + r0 + row] = acc;
+    if (perm) {
+      __syncthreads();   // rep_lds written; the previous pass's reads of row_lds done
+      if (on) *(bf16x8*)&row_lds[rr][chunk * 8] = *(const bf16x8*)(q + off);
+      __syncthreads();
+      if (on) {
+        bf16x8 y;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) y[j] = row_lds[rr][rep_lds[chunk * 8 + j] & (D - 1)];
+        *(bf16x8*)(qrep + off) = y;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBwdThreads) void bwd_dq_kernel(
+    const bf16* __restrict__ qrep, const bf16* __restrict__ k, const bf16* __restrict__ v,
+    const bf16* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
+    bf16* __restrict__ dq, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Nk, int Br, int Tq,
+    int Tw, int n_groups, int causal, float scale) {
+  constexpr int CH = D / 8;
+  constexpr int KS = D / 16;    // MFMA steps over the channels
+  constexpr int CB = D / 32;    // 32-channel blocks of the dQ~ accumulator
+  constexpr int TILE = kBwdStream * D * 2;
+  constexpr int SROW = D + 1;   // floats per row of the epilogue's staging
+  constexpr int POOL = kBwdStream * SROW * 4 > 2 * TILE ? kBwdStream * SROW * 4 : 2 * TILE;
+  __shared__ __attribute__((aligned(16))) char pool[POOL];
+  __shared__ uint8_t perm_lds[kBwdRows / 32][D];
+  __shared__ uint8_t group_lds[kBwdRows / 32][D];   // group whose sampled channel c is, else 255
+  char* k_lds = pool;
+  char* v_lds = pool + TILE;
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int lq = lane & 31, hh = lane >> 5;
+  const int t = blockIdx.x % Tw;
+  const size_t bh = blockIdx.x / Tw;
+  const int b = (int)(bh / H), h = (int)(bh % H);
+  const int hk = h / (H / Hkv);
+  const int r0 = t * kBwdRows;
+  const int rows = min(kBwdRows, N - r0);
+  const int q_abs = r0 + 32 * w + lq;
+  const bool active = q_abs < N;
+  const int shift = Nk - N;
+  const float sl2e = scale * kLog2e;
+
+  const bf16* kh = k + (size_t)(b * Hkv + hk) * Nk * D;
+  const bf16* vh = v + (size_t)(b * Hkv + hk) * Nk * D;
+  const size_t row_off = (bh * N + (active ? q_abs : r0)) * D;
+
+  bf16x8 qop[KS], doop[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    u32x4 x = {0u, 0u, 0u, 0u}, y = {0u, 0u, 0u, 0u};
+    if (active) {
+      x = *(const u32x4*)(qrep + row_off + (2 * s + hh) * 8);
+      y = *(const u32x4*)(dout + row_off + (2 * s + hh) * 8);
+    }
+    qop[s] = __builtin_bit_cast(bf16x8, x);
+    doop[s] = __builtin_bit_cast(bf16x8, y);
+  }
+  const float lse2 = active ? lse[bh * N + q_abs] * kLog2e : 0.0f;
+  const float dl = active ? delta[bh * N + q_abs] : 0.0f;
+  const int lim = causal ? min(q_abs + shift, Nk - 1) : Nk - 1;   // last key this row sees
+
+  f32x16 dqacc[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) zero(dqacc[cb]);
+
+  const int n_end = causal ? min(Nk, r0 + rows + shift) : Nk;
+  for (int n0 = 0; n0 < n_end; n0 += kBwdStream) {
+    __syncthreads();   // the previous tile's reads are done
+    stage_tile<D>(k_lds, kh, n0, Nk, tid);
+    stage_tile<D>(v_lds, vh, n0, Nk, tid);
+    __syncthreads();
+#pragma unroll
+    for (int mb = 0; mb < kBwdStream / 32; ++mb) {
+      f32x16 sacc, dpacc;
+      zero(sacc);
+      zero(dpacc);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        sacc = mfma(read_rows<D>(k_lds, 32 * mb + lq, s, hh), qop[s], sacc);
+        dpacc = mfma(read_rows<D>(v_lds, 32 * mb + lq, s, hh), doop[s], dpacc);
+      }
+      bf16x8 dsop[2];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int kv = n0 + 32 * mb + acc_row(i, hh);
+        const float p = kv <= lim ? __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -lse2)) : 0.0f;
+        dsop[i >> 3][i & 7] = (bf16)(p * (dpacc[i] - dl));
+      }
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+          dqacc[cb] = mfma(read_transposed<D>(k_lds, 32 * mb + 16 * tt, cb, lane), dsop[tt], dqacc[cb]);
+    }
+  }
+
+  // Epilogue: dQ~ of 64 rows at a time into LDS (float), then each wave sums, for every group of
+  // its rows' Q block, the members' columns into the sampled channel; the other channels get 0.
+  float* stage = (float*)pool;
+  const int G = D / n_groups;
+  {
+    const int blk = (r0 + 32 * w) / Br;   // a wave's 32 rows lie in one Q block (Br is a multiple of 32)
+    const uint8_t* pr = perm ? perm + (bh * Tq + min(blk, Tq - 1)) * D : nullptr;
+    for (int i = lane; i < D; i += 64) {
+      perm_lds[w][i] = pr ? (pr[i] & (D - 1)) : (uint8_t)i;
+      group_lds[w][i] = 255;
+    }
+  }
+  __syncthreads();
+  for (int j = lane; j < n_groups; j += 64) group_lds[w][perm_lds[w][j * G]] = (uint8_t)j;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    __syncthreads();   // the tiles' (the previous half's) reads are done; the tables are written
+    const int srow0 = 32 * (w & 1);
+    if ((w >> 1) == half) {
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) stage[(srow0 + lq) * SROW + 32 * cb + acc_row(i, hh)] = dqacc[cb][i];
+    }
+    __syncthreads();
+    if ((w >> 1) == half) {
+      for (int id = lane; id < 32 * CH; id += 64) {
+        const int lr = id / CH, chunk = id % CH;
+        const int row = r0 + 32 * w + lr;
+        if (row >= N) continue;
+        bf16x8 y;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int j = group_lds[w][chunk * 8 + e];
+          float s = 0.0f;
+          if (j != 255)
+            for (int m = 0; m < G; ++m) s += stage[(srow0 + lr) * SROW + perm_lds[w][j * G + m]];
+          y[e] = (bf16)(scale * s);
+        }
+        *(bf16x8*)(dq + (bh * N + row) * D + chunk * 8) = y;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
+    const bf16* __restrict__ qrep, const bf16* __restrict__ k, const bf16* __restrict__ v,
+    const bf16* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
+    bf16* __restrict__ dk, bf16* __restrict__ dv, int H, int Hkv, int N, int Nk, int Tw, int causal, float scale) {
+  constexpr int KS = D / 16;
+  constexpr int CB = D / 32;
+  constexpr int TILE = kBwdStream * D * 2;
+  __shared__ __attribute__((aligned(16))) char q_lds[TILE];
+  __shared__ __attribute__((aligned(16))) char do_lds[TILE];
+  __shared__ __attribute__((aligned(16))) float lse_lds[kBwdStream];   // lse * log2(e)
+  __shared__ __attribute__((aligned(16))) float dl_lds[kBwdStream];
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int lq = lane & 31, hh = lane >> 5;
+  const int t = blockIdx.x % Tw;
+  const size_t bk = blockIdx.x / Tw;   // b * Hkv + hk
+  const int b = (int)(bk / Hkv), hk = (int)(bk % Hkv);
+  const int rep = H / Hkv;
+  const int n0 = t * kBwdRows;
+  const int key = n0 + 32 * w + lq;
+  const bool valid = key < Nk;
+  const int shift = Nk - N;
+  const float sl2e = scale * kLog2e;
+
+  bf16x8 kop[KS], vop[KS];
+  {
+    const size_t row_off = (bk * Nk + (valid ? key : n0)) * D;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      u32x4 x = {0u, 0u, 0u, 0u}, y = {0u, 0u, 0u, 0u};
+      if (valid) {
+        x = *(const u32x4*)(k + row_off + (2 * s + hh) * 8);
+        y = *(const u32x4*)(v + row_off + (2 * s + hh) * 8);
+      }
+      kop[s] = __builtin_bit_cast(bf16x8, x);
+      vop[s] = __builtin_bit_cast(bf16x8, y);
+    }
+  }
+  f32x16 dkacc[CB], dvacc[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+    zero(dkacc[cb]);
+    zero(dvacc[cb]);
+  }
+  // causal: query i sees key n iff n <= i + shift; the first tile with a row that sees key n0
+  const int i_start = causal ? max(0, n0 - shift) / kBwdStream * kBwdStream : 0;
+
+  for (int h = hk * rep; h < (hk + 1) * rep; ++h) {
+    const size_t bh = (size_t)b * H + h;
+    const bf16* qh = qrep + bh * N * D;
+    const bf16* doh = dout + bh * N * D;
+    for (int i0 = i_start; i0 < N; i0 += kBwdStream) {
+      __syncthreads();   // the previous tile's reads are done
+      stage_tile<D>(q_lds, qh, i0, N, tid);
+      stage_tile<D>(do_lds, doh, i0, N, tid);
+      if (tid < kBwdStream) {
+        const bool on = i0 + tid < N;
+        lse_lds[tid] = on ? lse[bh * N + i0 + tid] * kLog2e : 0.0f;
+        dl_lds[tid] = on ? delta[bh * N + i0 + tid] : 0.0f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int qb = 0; qb < kBwdStream / 32; ++qb) {
+        f32x16 sacc, dpacc;
+        zero(sacc);
+        zero(dpacc);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          sacc = mfma(read_rows<D>(q_lds, 32 * qb + lq, s, hh), kop[s], sacc);
+          dpacc = mfma(read_rows<D>(do_lds, 32 * qb + lq, s, hh), vop[s], dpacc);
+        }
+        bf16x8 pop[2], dsop[2];
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const int rb = 32 * qb + 8 * i4 + 4 * hh;   // four consecutive rows
+          const f32x4 l4 = *(const f32x4*)&lse_lds[rb], d4 = *(const f32x4*)&dl_lds[rb];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int i = 4 * i4 + e;
+            const int qi = i0 + rb + e;
+            const bool vis = valid && qi < N && !(causal && key > qi + shift);
+            const float p = vis ? __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -l4[e])) : 0.0f;
+            pop[i >> 3][i & 7] = (bf16)p;
+            dsop[i >> 3][i & 7] = (bf16)(p * (dpacc[i] - d4[e]));
+          }
+        }
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            dvacc[cb] = mfma(read_transposed<D>(do_lds, 32 * qb + 16 * tt, cb, lane), pop[tt], dvacc[cb]);
+            dkacc[cb] = mfma(read_transposed<D>(q_lds, 32 * qb + 16 * tt, cb, lane), dsop[tt], dkacc[cb]);
+          }
+      }
+    }
+  }
+  if (valid) {
+    bf16* dkrow = dk + (bk * Nk + key) * D;
+    bf16* dvrow = dv + (bk * Nk + key) * D;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int c = 32 * cb + 8 * i4 + 4 * hh;
+        bf16x4 a, bq;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          a[e] = (bf16)(scale * dkacc[cb][4 * i4 + e]);
+          bq[e] = (bf16)dvacc[cb][4 * i4 + e];
+        }
+        *(bf16x4*)(dkrow + c) = a;
+        *(bf16x4*)(dvrow + c) = bq;
+      }
+  }
+}
+
+}  // namespace
+
+size_t attn_bf16_bwd_scratch_bytes(const Problem& pb, int distr) {
+  const size_t rows = (size_t)pb.B * pb.H * pb.N;
+  const size_t delta = (rows * 4 + 255) & ~(size_t)255;
+  return delta + (distr ? ((rows * pb.d * 2 + 255) & ~(size_t)255) : 0);
+}
+
+hipError_t launch_attn_bf16_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                                const float* lse, void* dq, void* dk, void* dv, const uint8_t* perm, void* scratch,
+                                const Problem& pb, int distr, hipStream_t stream) {
+  const int Tq = (pb.N + pb.Br - 1) / pb.Br;
+  const int Twq = (pb.N + kBwdRows - 1) / kBwdRows;
+  const int Twk = (pb.Nk + kBwdRows - 1) / kBwdRows;
+  const long long prep_units = (long long)pb.B * pb.H * Tq;
+  const long long q_units = (long long)pb.B * pb.H * Twq;
+  const long long k_units = (long long)pb.B * pb.Hkv * Twk;
+  if (prep_units > 0x7fffffffLL || q_units > 0x7fffffffLL || k_units > 0x7fffffffLL) return hipErrorInvalidValue;
+  if ((pb.d != 64 && pb.d != 128) || pb.Br % 32 != 0 || pb.d % pb.n_groups != 0) return hipErrorInvalidValue;
+  const size_t rows = (size_t)pb.B * pb.H * pb.N;
+  float* delta = (float*)scratch;
+  bf16* qrep = distr ? (bf16*)((char*)scratch + ((rows * 4 + 255) & ~(size_t)255)) : nullptr;
+  const uint8_t* table = distr ? perm : nullptr;
+  const bf16* qx = distr ? qrep : (const bf16*)q;
+  const int n_groups = distr ? pb.n_groups : pb.d;
+#define DA_BWD(DD)                                                                                                   \
+  do {                                                                                                               \
+    hipLaunchKernelGGL((bwd_prepare_kernel<DD>), dim3((unsigned)prep_units), dim3(kBwdThreads), 0, stream,           \
+                       (const bf16*)q, (const bf16*)o, (const bf16*)dout, table, qrep, delta, pb.N, pb.Br, Tq, n_groups); \
+    hipLaunchKernelGGL((bwd_dq_kernel<DD>), dim3((unsigned)q_units), dim3(kBwdThreads), 0, stream, qx, (const bf16*)k, \
+                       (const bf16*)v, (const bf16*)dout, lse, delta, (bf16*)dq, table, pb.H, pb.Hkv, pb.N, pb.Nk,   \
+                       pb.Br, Tq, Twq, n_groups, pb.causal, pb.scale);                                               \
+    hipLaunchKernelGGL((bwd_dkv_kernel<DD>), dim3((unsigned)k_units), dim3(kBwdThreads), 0, stream, qx,              \
+                       (const bf16*)k, (const bf16*)v, (const bf16*)dout, lse, delta, (bf16*)dk, (bf16*)dv, pb.H,    \
+                       pb.Hkv, pb.N, pb.Nk, Twk, pb.causal, pb.scale);                                               \
+  } while (0)
+  if (pb.d == 64) DA_BWD(64);
+  else DA_BWD(128);
+#undef DA_BWD
+  return hipGetLastError();
+}
+
+}  // namespace da

@@ -1,6 +1,6 @@
 // Backward of the attention forward (exact and DistrAttention) for gfx950 in float arithmetic on
-// the vector ALUs: the reference-precision path, for float tensors and (converted on load, rounded
-// on store) for bf16 tensors; two kernels, no atomics (results do not depend on the run).
+// the vector ALUs: the reference-precision path, for float tensors (bf16 tensors take the
+// matrix-core kernels of attn_bf16_bwd.hip); two kernels, no atomics (results do not depend on the run).
 //
 // The paper trains through the approximation (Sec. 4.3, 4.4) and gives no gradient. Computed
 // here: the derivative of the forward with every Q block's grouping held fixed (the permutation
@@ -315,9 +315,8 @@ static hipError_t launch_bwd_typed(const void* q, const void* k, const void* v, 
 
 hipError_t launch_attn_f32_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
                                const float* lse, void* dq, void* dk, void* dv, const uint8_t* perm,
-                               const Problem& pb, int dtype, int distr, hipStream_t stream) {
-  return dtype == 0 ? launch_bwd_typed<bf16>(q, k, v, o, dout, lse, dq, dk, dv, perm, pb, distr, stream)
-                    : launch_bwd_typed<float>(q, k, v, o, dout, lse, dq, dk, dv, perm, pb, distr, stream);
+                               const Problem& pb, int distr, hipStream_t stream) {
+  return launch_bwd_typed<float>(q, k, v, o, dout, lse, dq, dk, dv, perm, pb, distr, stream);
 }
 
 }  // namespace da

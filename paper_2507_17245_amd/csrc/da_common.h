@@ -67,7 +67,7 @@ struct Problem {
   int Nk;     // keys / values per head (N is the number of queries); causal: key n is visible
               // to query i iff n <= i + (Nk - N)
   int side;   // 0: sample Q, fuse K, one grouping per Q block; 1: sample K, fuse Q, one grouping
-              // per K block of Bc rows (float path only)
+              // per K block of Bc rows (float-arithmetic kernel)
   int Bc;     // rows of a K block (only side 1 depends on it)
   float* lse; // optional device [B][H][N]: log-sum-exp of every row's visible scores (natural log)
 };
@@ -86,11 +86,17 @@ hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, void* o
 hipError_t launch_attn_f32(const void* q, const void* k, const void* v, void* o, const uint8_t* perm,
                            const Problem& pb, int dtype, int distr, hipStream_t stream);
 bool attn_bf16_supported(const Problem& pb, int distr);
-// Backward in float arithmetic (tensors bf16 or float by dtype): dq [B][H][N][d], dk and dv
-// [B][Hkv][Nk][d] from the forward's inputs, its output
-// o, the output gradient dout and the forward's row statistics lse; perm as in launch_attn_f32.
+// Backward in float arithmetic on the vector ALUs (float tensors): dq [B][H][N][d], dk and dv
+// [B][Hkv][Nk][d] from the forward's inputs, its output o, the output gradient dout and the
+// forward's row statistics lse; perm as in launch_attn_f32.
 hipError_t launch_attn_f32_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
                                const float* lse, void* dq, void* dk, void* dv, const uint8_t* perm,
-                               const Problem& pb, int dtype, int distr, hipStream_t stream);
+                               const Problem& pb, int distr, hipStream_t stream);
+// The same for bf16 tensors on the matrix cores; `scratch` (256-byte aligned,
+// attn_bf16_bwd_scratch_bytes) carries D_i and the channel-replicated Q between its kernels.
+size_t attn_bf16_bwd_scratch_bytes(const Problem& pb, int distr);
+hipError_t launch_attn_bf16_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                                const float* lse, void* dq, void* dk, void* dv, const uint8_t* perm, void* scratch,
+                                const Problem& pb, int distr, hipStream_t stream);
 
 }  // namespace da

@@ -1,4 +1,4 @@
-"""GPU parity of the backward pass (float arithmetic; float and bf16 tensors) against the CPU oracle (gradient of the forward with the
+"""GPU parity of the backward pass (float tensors: float arithmetic on the vector ALUs; bf16 tensors: matrix-core kernels) against the CPU oracle (gradient of the forward with the
 grouping held fixed; the paper, Sec. 4.3-4.4, trains through the method without giving one)."""
 import numpy as np
 import pytest
@@ -93,14 +93,19 @@ BF16_CASES = [
     ("llama", dict(H=4, Hkv=2, N=100, Nk=260)),
     ("mid", dict(B=1, H=2, Hkv=2, N=260, n_groups=32)),
     ("long", dict(H=2, Hkv=1, N=200, Br=64)),
+    ("long", dict(H=2, Hkv=1, N=700)),                          # causal, several workgroups per head
+    ("llama", dict(H=4, Hkv=2, N=300, Br=256)),
+    ("vit", dict(B=2, H=2, Hkv=2, N=130, Nk=45)),               # fewer keys than one tile
+    ("mid", dict(B=1, H=2, Hkv=1, N=200, n_groups=16)),         # groups of eight channels
+    ("vit", dict(B=1, H=2, Hkv=2, N=129, n_groups=64)),         # one channel per group
+    ("vit", dict(B=1, H=2, Hkv=1, N=1, Nk=70)),                 # a single query row
 ]
 
 
 @pytest.mark.parametrize("base,kw", BF16_CASES, ids=[f"{b}-{i}" for i, (b, _) in enumerate(BF16_CASES)])
 def test_backward_on_bf16_tensors(base, kw):
-    """bf16 tensors through the same kernels (float arithmetic, converted on load, rounded on
-    store), fed the bf16 forward's output and row statistics: within the bf16 tolerances relative
-    to the gradient's scale."""
+    """bf16 tensors on the matrix cores, fed the bf16 forward's output and row statistics: within
+    the bf16 tolerances relative to the gradient's scale; the unsampled query columns exactly zero."""
     import gpu_util as U
     cfg = W.CONFIGS[base].scaled(**kw)
     print(f"case {cfg}", flush=True)
@@ -116,6 +121,47 @@ def test_backward_on_bf16_tensors(base, kw):
             unit = max(1.0, np.abs(r).max())
             print(f"  distr={distr} {what}: max-abs {err.max():.3g} mean-abs {err.mean():.3g} (largest gradient {np.abs(r).max():.3g})", flush=True)
             assert err.max() <= 2e-2 * unit and err.mean() <= 2e-3 * unit, f"{base} distr={distr} {what}"
+        if distr and cfg.n_groups < cfg.d:
+            _, perm, _ = oracle.lsh_group(q, p)
+            G = cfg.d // cfg.n_groups
+            for t in range(cfg.Tq):
+                unsampled = np.setdiff1d(np.arange(cfg.d), perm[0, 0, t, ::G])
+                assert np.all(got[0][0, 0, t * cfg.Br:(t + 1) * cfg.Br][:, unsampled] == 0.0)
+
+
+def test_bf16_backward_is_deterministic_and_takes_a_workspace():
+    import torch
+
+    import gpu_util as U
+    import paper_2507_17245_amd as da
+    cfg = W.CONFIGS["llama"].scaled(H=4, Hkv=2, N=333)
+    q, k, v = W.make(cfg)
+    dout = W.make_grad(cfg)
+    a = run_backward(cfg, q, k, v, dout, True)
+    b = run_backward(cfg, q, k, v, dout, True)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    # the same through a caller's workspace of exactly the size the library asks for
+    tq, tk, tv, tdo = (U.to_dev(x, cfg.dtype) for x in (q, k, v, dout))
+    o = torch.empty_like(tq)
+    lse = torch.empty((cfg.B, cfg.H, cfg.N), dtype=torch.float32, device="cuda")
+    p = da.make_params(tq, tk, tv, Br=cfg.Br, Bc=cfg.Bc, n_groups=cfg.n_groups, causal=cfg.causal,
+                       lsh_seed=cfg.lsh_seed, n_planes=cfg.n_planes, lse_out=lse)
+    da.distr_attn_fwd_ex(tq, tk, tv, o, p)
+    need = da.distr_attn_bwd_workspace_bytes(p)
+    assert need >= cfg.B * cfg.H * cfg.N * (4 + 2 * cfg.d)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    pw = da.make_params(tq, tk, tv, Br=cfg.Br, Bc=cfg.Bc, n_groups=cfg.n_groups, causal=cfg.causal,
+                        lsh_seed=cfg.lsh_seed, n_planes=cfg.n_planes, workspace=ws)
+    outs = [torch.full_like(t, float("nan")) for t in (tq, tk, tk)]
+    da.distr_attn_bwd_ex(tq, tk, tv, o, tdo, lse, *outs, pw)
+    torch.cuda.synchronize()
+    assert all(np.array_equal(x, t.float().cpu().numpy()) for x, t in zip(a, outs))
+    small = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+    ps = da.make_params(tq, tk, tv, Br=cfg.Br, Bc=cfg.Bc, n_groups=cfg.n_groups, causal=cfg.causal,
+                        lsh_seed=cfg.lsh_seed, n_planes=cfg.n_planes, workspace=small)
+    with pytest.raises(da.DistrAttnError) as e:
+        da.distr_attn_bwd_ex(tq, tk, tv, o, tdo, lse, *outs, ps)
+    assert e.value.code == da.DA_ERR_WORKSPACE
 
 
 def test_backward_refuses_the_mirrored_form():
