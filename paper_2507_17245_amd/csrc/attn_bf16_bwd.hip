@@ -13,7 +13,7 @@
 // sum over each group's members for dQ. P = exp(S^ - lse) is rebuilt from the forward's row
 // statistics, dP = dO V^T, D_i = sum_c dO_ic O_ic, dS = P o (dP - D), dV = P^T dO.
 //
-//   bwd_prepare_kernel  D_i for every row; Q~ (DistrAttention only) into scratch
+//   bwd_prepare_kernel  D_i and lse * log2(e) for every row; Q~ (DistrAttention only) into scratch
 //   bwd_dq_kernel       one workgroup per 128 query rows, lane = query row; K and V tiles of 64
 //                       rows stream through LDS:  S^T = K Q~^T, dP^T = V dO^T, dQ~^T += K^T dS^T
 //   bwd_dkv_kernel      one workgroup per 128 keys of a kv head, lane = key; Q~ and dO tiles of 64
@@ -21,7 +21,8 @@
 //                       S = Q~ K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q~^T dS
 // In both, the accumulator layout of the first products (registers = streamed rows, lanes =
 // resident rows) is the B-operand layout of the last ones, so P and dS never leave registers; the
-// streamed tiles are read once row-wise (16-byte reads) and once with transposing reads.
+// streamed tiles are read once row-wise (16-byte reads) and once with transposing reads. Tiles are
+// double-buffered in LDS and loaded one iteration ahead (one barrier per tile).
 #include "da_common.h"
 
 namespace da {
@@ -54,19 +55,37 @@ __device__ inline char* chunk_addr(char* tile, int row, int chunk) {
   return tile + row * (D * 2) + ((chunk ^ chunk_swz<D>(row)) << 4);
 }
 
-// rows [row0, row0 + 64) of a row-major [n_rows][D] bf16 matrix into an LDS tile, zeros past the end
+// Streamed tiles reach LDS by direct global->LDS loads (buffer_load ... lds: each wave-level load
+// drops 64 x 16 bytes contiguously): wave-level load j of wave w fills the 1 KB block 4*j + w of
+// the tile; the lane that owns a 16-byte position fetches the global chunk the swizzle assigns to
+// it. The source is a buffer descriptor over one head, whose range check makes rows past the end
+// read as zeros.
+typedef __attribute__((address_space(3))) void lds_void;
 template <int D>
-__device__ inline void stage_tile(char* tile, const bf16* __restrict__ src, int row0, int n_rows, int tid) {
-  constexpr int CH = D / 8;
+struct TileLoader {
+  static constexpr int CH = D / 8, ROWB = D * 2, TILE = kBwdStream * ROWB;
+  static constexpr int CPT = TILE / 1024 / (kBwdThreads / 64);
+  int voff[CPT];
+  int wave;
+  __device__ TileLoader(int wave_, int lane) : wave(wave_) {
 #pragma unroll
-  for (int it = 0; it < kBwdStream * CH / kBwdThreads; ++it) {
-    const int id = tid + it * kBwdThreads;
-    const int row = id / CH, chunk = id % CH;
-    u32x4 x = {0u, 0u, 0u, 0u};
-    if (row0 + row < n_rows) x = *(const u32x4*)(src + (size_t)(row0 + row) * D + chunk * 8);
-    *(u32x4*)chunk_addr<D>(tile, row, chunk) = x;
+    for (int j = 0; j < CPT; ++j) {
+      const int slot = (j * (kBwdThreads / 64) + wave) * 64 + lane;
+      const int row = slot / CH, pc = slot % CH;
+      voff[j] = row * ROWB + ((pc ^ chunk_swz<D>(row)) << 4);
+    }
   }
+  __device__ void load(__amdgpu_buffer_rsrc_t rsrc, int row0, char* dst) const {
+#pragma unroll
+    for (int j = 0; j < CPT; ++j)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(dst + (j * (kBwdThreads / 64) + wave) * 1024), 16,
+                                               voff[j], row0 * ROWB, 0, 0);
+  }
+};
+__device__ inline __amdgpu_buffer_rsrc_t head_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, bytes, 0x00020000);
 }
+__device__ inline void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // A operand, row-wise: row `row` of the tile, contraction slots 8*hh .. 8*hh+7 of step s
 template <int D>
@@ -99,14 +118,17 @@ __device__ inline void zero(f32x16& x) {
   for (int i = 0; i < 16; ++i) x[i] = 0.0f;
 }
 
+}  // namespace
+
 // ------------------------------------------------------------------------------------------------
-// D_i = sum_c dO_ic O_ic for every query row; for DistrAttention also Q~: channel c of a row takes
-// the value of the first channel (sorted order) of c's group in the row's Q block.
+// D_i = sum_c dO_ic O_ic and lse_i * log2(e) for every query row; for DistrAttention also Q~:
+// channel c of a row takes the value of the first channel (sorted order) of c's group in the
+// row's Q block.
 template <int D>
 __global__ __launch_bounds__(kBwdThreads) void bwd_prepare_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ o, const bf16* __restrict__ dout,
-    const uint8_t* __restrict__ perm, bf16* __restrict__ qrep, float* __restrict__ delta, int N, int Br, int Tq,
-    int n_groups) {
+    const float* __restrict__ lse, const uint8_t* __restrict__ perm, bf16* __restrict__ qrep,
+    float* __restrict__ delta, float* __restrict__ lse2, int N, int Br, int Tq, int n_groups) {
   constexpr int CH = D / 8;
   constexpr int RPP = kBwdThreads / CH;   // rows per pass
   __shared__ uint8_t rep_lds[D];
@@ -136,7 +158,10 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_prepare_kernel(
     }
 #pragma unroll
     for (int m = 1; m < CH; m <<= 1) acc += __shfl_xor(acc, m);
-    if (on && chunk == 0) delta[bh * N + r0 + row] = acc;
+    if (on && chunk == 0) {
+      delta[bh * N + r0 + row] = acc;
+      lse2[bh * N + r0 + row] = lse[bh * N + r0 + row] * kLog2e;
+    }
     if (perm) {
       __syncthreads();   // rep_lds written; the previous pass's reads of row_lds done
       if (on) *(bf16x8*)&row_lds[rr][chunk * 8] = *(const bf16x8*)(q + off);
@@ -153,26 +178,28 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_prepare_kernel(
 
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kBwdThreads) void bwd_dq_kernel(
+__global__ __launch_bounds__(kBwdThreads, 2) void bwd_dq_kernel(
     const bf16* __restrict__ qrep, const bf16* __restrict__ k, const bf16* __restrict__ v,
-    const bf16* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
+    const bf16* __restrict__ dout, const float* __restrict__ lse2p, const float* __restrict__ delta,
     bf16* __restrict__ dq, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Nk, int Br, int Tq,
     int Tw, int n_groups, int causal, float scale) {
   constexpr int CH = D / 8;
   constexpr int KS = D / 16;    // MFMA steps over the channels
   constexpr int CB = D / 32;    // 32-channel blocks of the dQ~ accumulator
   constexpr int TILE = kBwdStream * D * 2;
-  constexpr int SROW = D + 1;   // floats per row of the epilogue's staging
-  constexpr int POOL = kBwdStream * SROW * 4 > 2 * TILE ? kBwdStream * SROW * 4 : 2 * TILE;
-  __shared__ __attribute__((aligned(16))) char pool[POOL];
+  // separate objects: the compiler then does not make reads of one buffer wait for loads in
+  // flight into another
+  __shared__ __attribute__((aligned(1024))) char k_lds0[TILE];
+  __shared__ __attribute__((aligned(1024))) char k_lds1[TILE];
+  __shared__ __attribute__((aligned(1024))) char v_lds0[TILE];
+  __shared__ __attribute__((aligned(1024))) char v_lds1[TILE];
   __shared__ uint8_t perm_lds[kBwdRows / 32][D];
   __shared__ uint8_t group_lds[kBwdRows / 32][D];   // group whose sampled channel c is, else 255
-  char* k_lds = pool;
-  char* v_lds = pool + TILE;
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int lq = lane & 31, hh = lane >> 5;
-  const int t = blockIdx.x % Tw;
+  // causal: the blocks with the most keys first
+  const int t = causal ? Tw - 1 - (int)(blockIdx.x % Tw) : (int)(blockIdx.x % Tw);
   const size_t bh = blockIdx.x / Tw;
   const int b = (int)(bh / H), h = (int)(bh % H);
   const int hk = h / (H / Hkv);
@@ -183,10 +210,17 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dq_kernel(
   const int shift = Nk - N;
   const float sl2e = scale * kLog2e;
 
-  const bf16* kh = k + (size_t)(b * Hkv + hk) * Nk * D;
-  const bf16* vh = v + (size_t)(b * Hkv + hk) * Nk * D;
-  const size_t row_off = (bh * N + (active ? q_abs : r0)) * D;
+  const unsigned head_bytes = (unsigned)Nk * D * 2;
+  const __amdgpu_buffer_rsrc_t k_rsrc = head_rsrc(k + (size_t)(b * Hkv + hk) * Nk * D, head_bytes);
+  const __amdgpu_buffer_rsrc_t v_rsrc = head_rsrc(v + (size_t)(b * Hkv + hk) * Nk * D, head_bytes);
+  const TileLoader<D> loader(w, lane);
+  const int n_end = causal ? min(Nk, r0 + rows + shift) : Nk;
+  // tiles that end at or before n_free need no mask for any row of the workgroup
+  const int n_free = causal ? min(r0 + shift + 1, Nk) : Nk;
+  loader.load(k_rsrc, 0, k_lds0);
+  loader.load(v_rsrc, 0, v_lds0);
 
+  const size_t row_off = (bh * N + (active ? q_abs : r0)) * D;
   bf16x8 qop[KS], doop[KS];
 #pragma unroll
   for (int s = 0; s < KS; ++s) {
@@ -198,7 +232,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dq_kernel(
     qop[s] = __builtin_bit_cast(bf16x8, x);
     doop[s] = __builtin_bit_cast(bf16x8, y);
   }
-  const float lse2 = active ? lse[bh * N + q_abs] * kLog2e : 0.0f;
+  const float lse2 = active ? lse2p[bh * N + q_abs] : 0.0f;
   const float dl = active ? delta[bh * N + q_abs] : 0.0f;
   const int lim = causal ? min(q_abs + shift, Nk - 1) : Nk - 1;   // last key this row sees
 
@@ -206,12 +240,17 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dq_kernel(
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) zero(dqacc[cb]);
 
-  const int n_end = causal ? min(Nk, r0 + rows + shift) : Nk;
-  for (int n0 = 0; n0 < n_end; n0 += kBwdStream) {
-    __syncthreads();   // the previous tile's reads are done
-    stage_tile<D>(k_lds, kh, n0, Nk, tid);
-    stage_tile<D>(v_lds, vh, n0, Nk, tid);
-    __syncthreads();
+  int par = 0;
+  for (int n0 = 0; n0 < n_end; n0 += kBwdStream, par ^= 1) {
+    char* k_lds = par ? k_lds1 : k_lds0;
+    char* v_lds = par ? v_lds1 : v_lds0;
+    wait_loads();
+    __syncthreads();   // this tile has landed; the other buffers' readers are done
+    if (n0 + kBwdStream < n_end) {
+      loader.load(k_rsrc, n0 + kBwdStream, par ? k_lds0 : k_lds1);
+      loader.load(v_rsrc, n0 + kBwdStream, par ? v_lds0 : v_lds1);
+    }
+    const bool masked = n0 + kBwdStream > n_free;
 #pragma unroll
     for (int mb = 0; mb < kBwdStream / 32; ++mb) {
       f32x16 sacc, dpacc;
@@ -223,11 +262,19 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dq_kernel(
         dpacc = mfma(read_rows<D>(v_lds, 32 * mb + lq, s, hh), doop[s], dpacc);
       }
       bf16x8 dsop[2];
+      if (masked) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int kv = n0 + 32 * mb + acc_row(i, hh);
-        const float p = kv <= lim ? __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -lse2)) : 0.0f;
-        dsop[i >> 3][i & 7] = (bf16)(p * (dpacc[i] - dl));
+        for (int i = 0; i < 16; ++i) {
+          const int kv = n0 + 32 * mb + acc_row(i, hh);
+          const float p = kv <= lim ? __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -lse2)) : 0.0f;
+          dsop[i >> 3][i & 7] = (bf16)(p * (dpacc[i] - dl));
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -lse2));
+          dsop[i >> 3][i & 7] = (bf16)(p * (dpacc[i] - dl));
+        }
       }
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb)
@@ -237,9 +284,17 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dq_kernel(
     }
   }
 
-  // Epilogue: dQ~ of 64 rows at a time into LDS (float), then each wave sums, for every group of
-  // its rows' Q block, the members' columns into the sampled channel; the other channels get 0.
-  float* stage = (float*)pool;
+  // Epilogue: every wave puts the dQ~ of its 32 rows into LDS (float; the column index XORed
+  // with the row so that a register's 32 rows fall into different banks) and sums, for every
+  // group of its rows' Q block, the members' columns into the sampled channel; the other channels
+  // get 0.
+  __syncthreads();   // all waves are done with the tiles
+  float* stage = (float*)(w == 0 ? k_lds0 : w == 1 ? k_lds1 : w == 2 ? v_lds0 : v_lds1);
+  static_assert(32 * D * 4 <= TILE, "a wave's staging fits one tile buffer");
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) stage[lq * D + ((32 * cb + acc_row(i, hh)) ^ lq)] = dqacc[cb][i];
   const int G = D / n_groups;
   {
     const int blk = (r0 + 32 * w) / Br;   // a wave's 32 rows lie in one Q block (Br is a multiple of 32)
@@ -251,50 +306,67 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dq_kernel(
   }
   __syncthreads();
   for (int j = lane; j < n_groups; j += 64) group_lds[w][perm_lds[w][j * G]] = (uint8_t)j;
+  __syncthreads();
+  for (int id = lane; id < 32 * CH; id += 64) {
+    const int lr = id / CH, chunk = id % CH;
+    const int row = r0 + 32 * w + lr;
+    if (row >= N) continue;
+    bf16x8 y;
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    __syncthreads();   // the tiles' (the previous half's) reads are done; the tables are written
-    const int srow0 = 32 * (w & 1);
-    if ((w >> 1) == half) {
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) stage[(srow0 + lq) * SROW + 32 * cb + acc_row(i, hh)] = dqacc[cb][i];
+    for (int e = 0; e < 8; ++e) {
+      const int j = group_lds[w][chunk * 8 + e];
+      float s = 0.0f;
+      if (j != 255)
+        for (int m = 0; m < G; ++m) s += stage[lr * D + (perm_lds[w][j * G + m] ^ lr)];
+      y[e] = (bf16)(scale * s);
     }
-    __syncthreads();
-    if ((w >> 1) == half) {
-      for (int id = lane; id < 32 * CH; id += 64) {
-        const int lr = id / CH, chunk = id % CH;
-        const int row = r0 + 32 * w + lr;
-        if (row >= N) continue;
-        bf16x8 y;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int j = group_lds[w][chunk * 8 + e];
-          float s = 0.0f;
-          if (j != 255)
-            for (int m = 0; m < G; ++m) s += stage[(srow0 + lr) * SROW + perm_lds[w][j * G + m]];
-          y[e] = (bf16)(scale * s);
-        }
-        *(bf16x8*)(dq + (bh * N + row) * D + chunk * 8) = y;
-      }
-    }
+    *(bf16x8*)(dq + (bh * N + row) * D + chunk * 8) = y;
   }
 }
+
+// What the dK/dV kernel streams: iteration `it` brings rows i_start + 64 * (it % tiles) .. of
+// query head h0 + it / tiles (Q~, dO, and the rows' statistics) into the buffers of parity `par`.
+template <int D>
+struct QueryStream {
+  const bf16 *qrep, *dout;
+  const float *lse2, *delta;
+  char *q_lds[2], *do_lds[2];
+  float *lse_lds[2], *dl_lds[2];
+  size_t bh0;   // b * H + first query head of the kv head
+  int N, i_start, tiles, wave, lane;
+  TileLoader<D> loader;
+  __device__ void issue(int it, int par) const {
+    const size_t bh = bh0 + it / tiles;
+    const int i0 = i_start + kBwdStream * (it % tiles);
+    const unsigned head_bytes = (unsigned)N * D * 2;
+    loader.load(head_rsrc(qrep + bh * N * D, head_bytes), i0, q_lds[par]);
+    loader.load(head_rsrc(dout + bh * N * D, head_bytes), i0, do_lds[par]);
+    if (wave == 0)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(head_rsrc(lse2 + bh * N, (unsigned)N * 4), (lds_void*)lse_lds[par], 4,
+                                               lane * 4, i0 * 4, 0, 0);
+    if (wave == 1)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(head_rsrc(delta + bh * N, (unsigned)N * 4), (lds_void*)dl_lds[par], 4,
+                                               lane * 4, i0 * 4, 0, 0);
+  }
+};
 
 // ------------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
     const bf16* __restrict__ qrep, const bf16* __restrict__ k, const bf16* __restrict__ v,
-    const bf16* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
+    const bf16* __restrict__ dout, const float* __restrict__ lse2p, const float* __restrict__ delta,
     bf16* __restrict__ dk, bf16* __restrict__ dv, int H, int Hkv, int N, int Nk, int Tw, int causal, float scale) {
   constexpr int KS = D / 16;
   constexpr int CB = D / 32;
   constexpr int TILE = kBwdStream * D * 2;
-  __shared__ __attribute__((aligned(16))) char q_lds[TILE];
-  __shared__ __attribute__((aligned(16))) char do_lds[TILE];
-  __shared__ __attribute__((aligned(16))) float lse_lds[kBwdStream];   // lse * log2(e)
-  __shared__ __attribute__((aligned(16))) float dl_lds[kBwdStream];
+  __shared__ __attribute__((aligned(1024))) char q_lds0[TILE];
+  __shared__ __attribute__((aligned(1024))) char q_lds1[TILE];
+  __shared__ __attribute__((aligned(1024))) char do_lds0[TILE];
+  __shared__ __attribute__((aligned(1024))) char do_lds1[TILE];
+  __shared__ __attribute__((aligned(256))) float lse_lds0[kBwdStream];   // lse * log2(e)
+  __shared__ __attribute__((aligned(256))) float lse_lds1[kBwdStream];
+  __shared__ __attribute__((aligned(256))) float dl_lds0[kBwdStream];
+  __shared__ __attribute__((aligned(256))) float dl_lds1[kBwdStream];
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int lq = lane & 31, hh = lane >> 5;
@@ -307,6 +379,15 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
   const bool valid = key < Nk;
   const int shift = Nk - N;
   const float sl2e = scale * kLog2e;
+
+  // causal: query i sees key n iff n <= i + shift; the first tile with a row that sees key n0
+  const int i_start = causal ? max(0, n0 - shift) / kBwdStream * kBwdStream : 0;
+  const int tiles = (N - i_start + kBwdStream - 1) / kBwdStream;   // per query head
+  const int n_it = rep * tiles;
+  const TileLoader<D> loader(w, lane);
+  const QueryStream<D> ctx = {qrep, dout, lse2p, delta, {q_lds0, q_lds1}, {do_lds0, do_lds1}, {lse_lds0, lse_lds1},
+                              {dl_lds0, dl_lds1}, (size_t)b * H + hk * rep, N, i_start, tiles, w, lane, loader};
+  ctx.issue(0, 0);
 
   bf16x8 kop[KS], vop[KS];
   {
@@ -328,56 +409,53 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
     zero(dkacc[cb]);
     zero(dvacc[cb]);
   }
-  // causal: query i sees key n iff n <= i + shift; the first tile with a row that sees key n0
-  const int i_start = causal ? max(0, n0 - shift) / kBwdStream * kBwdStream : 0;
 
-  for (int h = hk * rep; h < (hk + 1) * rep; ++h) {
-    const size_t bh = (size_t)b * H + h;
-    const bf16* qh = qrep + bh * N * D;
-    const bf16* doh = dout + bh * N * D;
-    for (int i0 = i_start; i0 < N; i0 += kBwdStream) {
-      __syncthreads();   // the previous tile's reads are done
-      stage_tile<D>(q_lds, qh, i0, N, tid);
-      stage_tile<D>(do_lds, doh, i0, N, tid);
-      if (tid < kBwdStream) {
-        const bool on = i0 + tid < N;
-        lse_lds[tid] = on ? lse[bh * N + i0 + tid] * kLog2e : 0.0f;
-        dl_lds[tid] = on ? delta[bh * N + i0 + tid] : 0.0f;
+  for (int it = 0; it < n_it; ++it) {
+    const int par = it & 1;
+    char* q_lds = par ? q_lds1 : q_lds0;
+    char* do_lds = par ? do_lds1 : do_lds0;
+    const float* lse_lds = par ? lse_lds1 : lse_lds0;
+    const float* dl_lds = par ? dl_lds1 : dl_lds0;
+    const int i0 = i_start + kBwdStream * (it % tiles);
+    wait_loads();
+    __syncthreads();   // this tile has landed; the other buffers' readers are done
+    if (it + 1 < n_it) ctx.issue(it + 1, par ^ 1);
+    // no mask: every row is a query, every key of the workgroup exists and is visible to all rows
+    const bool masked = i0 + kBwdStream > N || n0 + kBwdRows > Nk || (causal && n0 + kBwdRows - 1 > i0 + shift);
+#pragma unroll
+    for (int qb = 0; qb < kBwdStream / 32; ++qb) {
+      f32x16 sacc, dpacc;
+      zero(sacc);
+      zero(dpacc);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        sacc = mfma(read_rows<D>(q_lds, 32 * qb + lq, s, hh), kop[s], sacc);
+        dpacc = mfma(read_rows<D>(do_lds, 32 * qb + lq, s, hh), vop[s], dpacc);
       }
-      __syncthreads();
+      bf16x8 pop[2], dsop[2];
 #pragma unroll
-      for (int qb = 0; qb < kBwdStream / 32; ++qb) {
-        f32x16 sacc, dpacc;
-        zero(sacc);
-        zero(dpacc);
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int rb = 32 * qb + 8 * i4 + 4 * hh;   // four consecutive rows
+        const f32x4 l4 = *(const f32x4*)&lse_lds[rb], d4 = *(const f32x4*)&dl_lds[rb];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          sacc = mfma(read_rows<D>(q_lds, 32 * qb + lq, s, hh), kop[s], sacc);
-          dpacc = mfma(read_rows<D>(do_lds, 32 * qb + lq, s, hh), vop[s], dpacc);
-        }
-        bf16x8 pop[2], dsop[2];
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const int rb = 32 * qb + 8 * i4 + 4 * hh;   // four consecutive rows
-          const f32x4 l4 = *(const f32x4*)&lse_lds[rb], d4 = *(const f32x4*)&dl_lds[rb];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int i = 4 * i4 + e;
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * i4 + e;
+          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -l4[e]));
+          if (masked) {
             const int qi = i0 + rb + e;
-            const bool vis = valid && qi < N && !(causal && key > qi + shift);
-            const float p = vis ? __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -l4[e])) : 0.0f;
-            pop[i >> 3][i & 7] = (bf16)p;
-            dsop[i >> 3][i & 7] = (bf16)(p * (dpacc[i] - d4[e]));
+            if (!(valid && qi < N && !(causal && key > qi + shift))) p = 0.0f;
           }
+          pop[i >> 3][i & 7] = (bf16)p;
+          dsop[i >> 3][i & 7] = (bf16)(p * (dpacc[i] - d4[e]));
         }
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-          for (int tt = 0; tt < 2; ++tt) {
-            dvacc[cb] = mfma(read_transposed<D>(do_lds, 32 * qb + 16 * tt, cb, lane), pop[tt], dvacc[cb]);
-            dkacc[cb] = mfma(read_transposed<D>(q_lds, 32 * qb + 16 * tt, cb, lane), dsop[tt], dkacc[cb]);
-          }
       }
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          dvacc[cb] = mfma(read_transposed<D>(do_lds, 32 * qb + 16 * tt, cb, lane), pop[tt], dvacc[cb]);
+          dkacc[cb] = mfma(read_transposed<D>(q_lds, 32 * qb + 16 * tt, cb, lane), dsop[tt], dkacc[cb]);
+        }
     }
   }
   if (valid) {
@@ -400,12 +478,10 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
   }
 }
 
-}  // namespace
-
 size_t attn_bf16_bwd_scratch_bytes(const Problem& pb, int distr) {
   const size_t rows = (size_t)pb.B * pb.H * pb.N;
-  const size_t delta = (rows * 4 + 255) & ~(size_t)255;
-  return delta + (distr ? ((rows * pb.d * 2 + 255) & ~(size_t)255) : 0);
+  const size_t stat = (rows * 4 + 255) & ~(size_t)255;   // D_i, and lse * log2(e)
+  return 2 * stat + (distr ? ((rows * pb.d * 2 + 255) & ~(size_t)255) : 0);
 }
 
 hipError_t launch_attn_bf16_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
@@ -419,21 +495,25 @@ hipError_t launch_attn_bf16_bwd(const void* q, const void* k, const void* v, con
   const long long k_units = (long long)pb.B * pb.Hkv * Twk;
   if (prep_units > 0x7fffffffLL || q_units > 0x7fffffffLL || k_units > 0x7fffffffLL) return hipErrorInvalidValue;
   if ((pb.d != 64 && pb.d != 128) || pb.Br % 32 != 0 || pb.d % pb.n_groups != 0) return hipErrorInvalidValue;
+  // tiles are addressed by 32-bit byte offsets inside a head
+  if ((size_t)pb.N * pb.d * 2 >= 0x7fffffffULL || (size_t)pb.Nk * pb.d * 2 >= 0x7fffffffULL) return hipErrorInvalidValue;
   const size_t rows = (size_t)pb.B * pb.H * pb.N;
+  const size_t stat = (rows * 4 + 255) & ~(size_t)255;
   float* delta = (float*)scratch;
-  bf16* qrep = distr ? (bf16*)((char*)scratch + ((rows * 4 + 255) & ~(size_t)255)) : nullptr;
+  float* lse2 = (float*)((char*)scratch + stat);
+  bf16* qrep = distr ? (bf16*)((char*)scratch + 2 * stat) : nullptr;
   const uint8_t* table = distr ? perm : nullptr;
   const bf16* qx = distr ? qrep : (const bf16*)q;
   const int n_groups = distr ? pb.n_groups : pb.d;
 #define DA_BWD(DD)                                                                                                   \
   do {                                                                                                               \
     hipLaunchKernelGGL((bwd_prepare_kernel<DD>), dim3((unsigned)prep_units), dim3(kBwdThreads), 0, stream,           \
-                       (const bf16*)q, (const bf16*)o, (const bf16*)dout, table, qrep, delta, pb.N, pb.Br, Tq, n_groups); \
+                       (const bf16*)q, (const bf16*)o, (const bf16*)dout, lse, table, qrep, delta, lse2, pb.N, pb.Br, Tq, n_groups); \
     hipLaunchKernelGGL((bwd_dq_kernel<DD>), dim3((unsigned)q_units), dim3(kBwdThreads), 0, stream, qx, (const bf16*)k, \
-                       (const bf16*)v, (const bf16*)dout, lse, delta, (bf16*)dq, table, pb.H, pb.Hkv, pb.N, pb.Nk,   \
+                       (const bf16*)v, (const bf16*)dout, lse2, delta, (bf16*)dq, table, pb.H, pb.Hkv, pb.N, pb.Nk,   \
                        pb.Br, Tq, Twq, n_groups, pb.causal, pb.scale);                                               \
     hipLaunchKernelGGL((bwd_dkv_kernel<DD>), dim3((unsigned)k_units), dim3(kBwdThreads), 0, stream, qx,              \
-                       (const bf16*)k, (const bf16*)v, (const bf16*)dout, lse, delta, (bf16*)dk, (bf16*)dv, pb.H,    \
+                       (const bf16*)k, (const bf16*)v, (const bf16*)dout, lse2, delta, (bf16*)dk, (bf16*)dv, pb.H,    \
                        pb.Hkv, pb.N, pb.Nk, Twk, pb.causal, pb.scale);                                               \
   } while (0)
   if (pb.d == 64) DA_BWD(64);
