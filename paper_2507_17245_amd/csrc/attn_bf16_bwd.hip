@@ -23,6 +23,8 @@
 // resident rows) is the B-operand layout of the last ones, so P and dS never leave registers; the
 // streamed tiles are read once row-wise (16-byte reads) and once with transposing reads. Tiles are
 // double-buffered in LDS and loaded one iteration ahead (one barrier per tile).
+#include <type_traits>
+
 #include "da_common.h"
 
 namespace da {
@@ -87,28 +89,61 @@ __device__ inline __amdgpu_buffer_rsrc_t head_rsrc(const void* base, unsigned by
 }
 __device__ inline void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// A operand, row-wise: row `row` of the tile, contraction slots 8*hh .. 8*hh+7 of step s
+// Per-lane byte offsets of the MFMA A operands inside a streamed tile (the swizzle depends on the
+// low four bits of the row only, so a 32-row block or a 16-row step adds a multiple of the row
+// length).
+//  rows[s]:   row-wise operand of contraction step s: the 16-byte chunk 2*s + hh of tile row
+//             lane%32 (contraction slots 8*hh .. 8*hh+7 of the step).
+//  tr[cb][.]: operand of a product that contracts over the tile's rows (the tile transposed):
+//             output rows are the channels 32*cb + lane%32, the contraction runs over 16 tile rows
+//             in the order an accumulator enumerates them (slot j of lane half hh = row
+//             8*(j/4) + 4*hh + j%4), read by two ds_read_b64_tr_b16 (within 16 lanes, lane i
+//             receives element i%4 of the 8-byte pieces addressed by lanes 4j + i/4, j = 0..3):
+//             this lane addresses rows 4*hh + (lane%16)/4 and that + 8.
 template <int D>
-__device__ inline bf16x8 read_rows(char* tile, int row, int s, int hh) {
-  return *(const bf16x8*)chunk_addr<D>(tile, row, 2 * s + hh);
+struct OperandOffsets {
+  int rows[D / 16];
+  int tr[D / 32][2];
+  __device__ OperandOffsets(int lane) {
+    const int lq = lane & 31, hh = lane >> 5;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) rows[s] = (int)(chunk_addr<D>(nullptr, lq, 2 * s + hh) - (char*)nullptr);
+    const int row = 4 * hh + ((lane & 15) >> 2);
+    const int inb = 8 * (lane & 1);
+#pragma unroll
+    for (int cb = 0; cb < D / 32; ++cb) {
+      const int chunk = 4 * cb + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+      tr[cb][0] = (int)(chunk_addr<D>(nullptr, row, chunk) - (char*)nullptr) + inb;
+      tr[cb][1] = (int)(chunk_addr<D>(nullptr, row + 8, chunk) - (char*)nullptr) + inb;
+    }
+  }
+};
+
+// all row-wise operands of the 32-row block `blk` of a tile
+template <int D>
+__device__ inline void read_rows(const char* tile, int blk, const OperandOffsets<D>& off, bf16x8 (&a)[D / 16]) {
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) a[s] = *(const bf16x8*)(tile + blk * 32 * (D * 2) + off.rows[s]);
 }
 
-// A operand of a product that contracts over the tile's rows (the tile transposed): output rows
-// are the channels 32*cb + lane%32, the contraction runs over the 16 tile rows from rb on, in the
-// order an accumulator enumerates them (slot j of lane half hh = row 8*(j/4) + 4*hh + j%4).
-// Two ds_read_b64_tr_b16: within 16 lanes, lane i receives element i%4 of the 8-byte pieces
-// addressed by lanes 4j + i/4, j = 0..3.
+// all transposed operands of the 32-row block `blk`: [channel block][16-row step]
 template <int D>
-__device__ inline bf16x8 read_transposed(char* tile, int rb, int cb, int lane) {
-  const int hh = lane >> 5;
-  const int row = rb + 4 * hh + ((lane & 15) >> 2);
-  const int chunk = 4 * cb + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-  const int inb = 8 * (lane & 1);
-  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(chunk_addr<D>(tile, row, chunk) + inb));
-  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(chunk_addr<D>(tile, row + 8, chunk) + inb));
-  s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-  return __builtin_bit_cast(bf16x8, r);
+__device__ inline void read_transposed(const char* tile, int blk, const OperandOffsets<D>& off,
+                                       bf16x8 (&a)[D / 32][2]) {
+#pragma unroll
+  for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const char* base = tile + (blk * 32 + tt * 16) * (D * 2);
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + off.tr[cb][0]));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + off.tr[cb][1]));
+      s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      a[cb][tt] = __builtin_bit_cast(bf16x8, r);
+    }
 }
+
+// nothing moves across: operand reads issued before it stay ahead of the MFMAs behind it
+__device__ inline void fence() { __builtin_amdgcn_sched_barrier(0); }
 
 // tile row that register i of a 32 x 32 accumulator block holds, for lane half hh
 __device__ inline int acc_row(int i, int hh) { return 8 * (i >> 2) + 4 * hh + (i & 3); }
@@ -178,7 +213,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_prepare_kernel(
 
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kBwdThreads, 2) void bwd_dq_kernel(
+__global__ __launch_bounds__(kBwdThreads, (D == 128 ? 1 : 2)) void bwd_dq_kernel(
     const bf16* __restrict__ qrep, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ dout, const float* __restrict__ lse2p, const float* __restrict__ delta,
     bf16* __restrict__ dq, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Nk, int Br, int Tq,
@@ -240,10 +275,50 @@ __global__ __launch_bounds__(kBwdThreads, 2) void bwd_dq_kernel(
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) zero(dqacc[cb]);
 
-  int par = 0;
-  for (int n0 = 0; n0 < n_end; n0 += kBwdStream, par ^= 1) {
-    char* k_lds = par ? k_lds1 : k_lds0;
-    char* v_lds = par ? v_lds1 : v_lds0;
+  const OperandOffsets<D> off(lane);
+  // one 32-key block: S^T and dP^T from the operands already read, then dS^T as B operands
+  auto scores = [&](const bf16x8 (&ak)[KS], const bf16x8 (&av)[KS], f32x16& sacc, f32x16& dpacc) {
+    zero(sacc);
+    zero(dpacc);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      sacc = mfma(ak[s], qop[s], sacc);
+      dpacc = mfma(av[s], doop[s], dpacc);
+    }
+  };
+  auto ds_operands = [&](const f32x16& sacc, const f32x16& dpacc, int kv0, bool masked, bf16x8 (&dsop)[2]) {
+    float pv[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -lse2));
+    if (masked) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) pv[i] = kv0 + acc_row(i, hh) <= lim ? pv[i] : 0.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dsop[i >> 3][i & 7] = (bf16)(pv[i] * (dpacc[i] - dl));
+  };
+  auto dq_update = [&](const bf16x8 (&at)[CB][2], const bf16x8 (&dsop)[2]) {
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) dqacc[cb] = mfma(at[cb][tt], dsop[tt], dqacc[cb]);
+  };
+
+  // One tile; the loop is unrolled by two so that every buffer is a fixed object in each copy
+  // (the compiler then knows that the loads in flight do not touch the tile being read).
+  auto tile_step = [&](auto par_c, int n0) {
+    constexpr int par = decltype(par_c)::value;
+    const char* k_lds = par ? k_lds1 : k_lds0;
+    const char* v_lds = par ? v_lds1 : v_lds0;
+    if constexpr (D == 128) {
+      // Register classes, stated once per tile (one wave per SIMD, both halves of the register
+      // file in use): the dQ~ accumulators live in the accumulator half, the resident Q~ and dO
+      // operands in the vector half.
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) asm volatile("" : "+a"(dqacc[cb]));
+#pragma unroll
+      for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qop[s]), "+v"(doop[s]));
+    }
     wait_loads();
     __syncthreads();   // this tile has landed; the other buffers' readers are done
     if (n0 + kBwdStream < n_end) {
@@ -251,37 +326,30 @@ __global__ __launch_bounds__(kBwdThreads, 2) void bwd_dq_kernel(
       loader.load(v_rsrc, n0 + kBwdStream, par ? v_lds0 : v_lds1);
     }
     const bool masked = n0 + kBwdStream > n_free;
-#pragma unroll
-    for (int mb = 0; mb < kBwdStream / 32; ++mb) {
-      f32x16 sacc, dpacc;
-      zero(sacc);
-      zero(dpacc);
-#pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        sacc = mfma(read_rows<D>(k_lds, 32 * mb + lq, s, hh), qop[s], sacc);
-        dpacc = mfma(read_rows<D>(v_lds, 32 * mb + lq, s, hh), doop[s], dpacc);
-      }
-      bf16x8 dsop[2];
-      if (masked) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int kv = n0 + 32 * mb + acc_row(i, hh);
-          const float p = kv <= lim ? __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -lse2)) : 0.0f;
-          dsop[i >> 3][i & 7] = (bf16)(p * (dpacc[i] - dl));
-        }
-      } else {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -lse2));
-          dsop[i >> 3][i & 7] = (bf16)(p * (dpacc[i] - dl));
-        }
-      }
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-          dqacc[cb] = mfma(read_transposed<D>(k_lds, 32 * mb + 16 * tt, cb, lane), dsop[tt], dqacc[cb]);
-    }
+    // Operands are read a phase ahead of the MFMAs that take them; the vector work of a block
+    // sits next to the matrix work of the other one.
+    bf16x8 ak[KS], av[KS], at[CB][2], ds0[2], ds1[2];
+    f32x16 s0, p0, s1, p1;
+    read_rows<D>(k_lds, 0, off, ak);
+    read_rows<D>(v_lds, 0, off, av);
+    fence();
+    scores(ak, av, s0, p0);
+    read_rows<D>(k_lds, 1, off, ak);
+    read_rows<D>(v_lds, 1, off, av);
+    fence();
+    scores(ak, av, s1, p1);
+    ds_operands(s0, p0, n0, masked, ds0);
+    read_transposed<D>(k_lds, 0, off, at);
+    fence();
+    dq_update(at, ds0);
+    ds_operands(s1, p1, n0 + 32, masked, ds1);
+    read_transposed<D>(k_lds, 1, off, at);
+    fence();
+    dq_update(at, ds1);
+  };
+  for (int n0 = 0; n0 < n_end; n0 += 2 * kBwdStream) {
+    tile_step(std::integral_constant<int, 0>(), n0);
+    if (n0 + kBwdStream < n_end) tile_step(std::integral_constant<int, 1>(), n0 + kBwdStream);
   }
 
   // Epilogue: every wave puts the dQ~ of its 32 rows into LDS (float; the column index XORed
@@ -325,27 +393,25 @@ __global__ __launch_bounds__(kBwdThreads, 2) void bwd_dq_kernel(
 }
 
 // What the dK/dV kernel streams: iteration `it` brings rows i_start + 64 * (it % tiles) .. of
-// query head h0 + it / tiles (Q~, dO, and the rows' statistics) into the buffers of parity `par`.
+// query head bh0 + it / tiles (Q~, dO, and the rows' statistics) into the given buffers.
 template <int D>
 struct QueryStream {
   const bf16 *qrep, *dout;
   const float *lse2, *delta;
-  char *q_lds[2], *do_lds[2];
-  float *lse_lds[2], *dl_lds[2];
   size_t bh0;   // b * H + first query head of the kv head
   int N, i_start, tiles, wave, lane;
   TileLoader<D> loader;
-  __device__ void issue(int it, int par) const {
+  __device__ void issue(int it, char* q_dst, char* do_dst, float* lse_dst, float* dl_dst) const {
     const size_t bh = bh0 + it / tiles;
     const int i0 = i_start + kBwdStream * (it % tiles);
     const unsigned head_bytes = (unsigned)N * D * 2;
-    loader.load(head_rsrc(qrep + bh * N * D, head_bytes), i0, q_lds[par]);
-    loader.load(head_rsrc(dout + bh * N * D, head_bytes), i0, do_lds[par]);
+    loader.load(head_rsrc(qrep + bh * N * D, head_bytes), i0, q_dst);
+    loader.load(head_rsrc(dout + bh * N * D, head_bytes), i0, do_dst);
     if (wave == 0)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(head_rsrc(lse2 + bh * N, (unsigned)N * 4), (lds_void*)lse_lds[par], 4,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(head_rsrc(lse2 + bh * N, (unsigned)N * 4), (lds_void*)lse_dst, 4,
                                                lane * 4, i0 * 4, 0, 0);
     if (wave == 1)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(head_rsrc(delta + bh * N, (unsigned)N * 4), (lds_void*)dl_lds[par], 4,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(head_rsrc(delta + bh * N, (unsigned)N * 4), (lds_void*)dl_dst, 4,
                                                lane * 4, i0 * 4, 0, 0);
   }
 };
@@ -385,9 +451,8 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
   const int tiles = (N - i_start + kBwdStream - 1) / kBwdStream;   // per query head
   const int n_it = rep * tiles;
   const TileLoader<D> loader(w, lane);
-  const QueryStream<D> ctx = {qrep, dout, lse2p, delta, {q_lds0, q_lds1}, {do_lds0, do_lds1}, {lse_lds0, lse_lds1},
-                              {dl_lds0, dl_lds1}, (size_t)b * H + hk * rep, N, i_start, tiles, w, lane, loader};
-  ctx.issue(0, 0);
+  const QueryStream<D> ctx = {qrep, dout, lse2p, delta, (size_t)b * H + hk * rep, N, i_start, tiles, w, lane, loader};
+  ctx.issue(0, q_lds0, do_lds0, lse_lds0, dl_lds0);
 
   bf16x8 kop[KS], vop[KS];
   {
@@ -410,53 +475,105 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
     zero(dvacc[cb]);
   }
 
-  for (int it = 0; it < n_it; ++it) {
-    const int par = it & 1;
-    char* q_lds = par ? q_lds1 : q_lds0;
-    char* do_lds = par ? do_lds1 : do_lds0;
+  const OperandOffsets<D> off(lane);
+  // One tile; the loop is unrolled by two so that every buffer is a fixed object in each copy
+  // (the compiler then knows that the loads in flight do not touch the tile being read).
+  auto tile_step = [&](auto par_c, int it) {
+    constexpr int par = decltype(par_c)::value;
+    const char* q_lds = par ? q_lds1 : q_lds0;
+    const char* do_lds = par ? do_lds1 : do_lds0;
     const float* lse_lds = par ? lse_lds1 : lse_lds0;
     const float* dl_lds = par ? dl_lds1 : dl_lds0;
     const int i0 = i_start + kBwdStream * (it % tiles);
+    // Register classes, stated once per tile: the accumulators of dK and dV live in the
+    // accumulator half of the register file, the resident K and V operands in the vector half
+    // (left to itself the allocator moved 128 accumulator registers back and forth per tile).
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) asm volatile("" : "+a"(dkacc[cb]), "+a"(dvacc[cb]));
+#pragma unroll
+    for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(kop[s]), "+v"(vop[s]));
     wait_loads();
     __syncthreads();   // this tile has landed; the other buffers' readers are done
-    if (it + 1 < n_it) ctx.issue(it + 1, par ^ 1);
+    if (it + 1 < n_it) {
+      if constexpr (par) ctx.issue(it + 1, q_lds0, do_lds0, lse_lds0, dl_lds0);
+      else ctx.issue(it + 1, q_lds1, do_lds1, lse_lds1, dl_lds1);
+    }
     // no mask: every row is a query, every key of the workgroup exists and is visible to all rows
     const bool masked = i0 + kBwdStream > N || n0 + kBwdRows > Nk || (causal && n0 + kBwdRows - 1 > i0 + shift);
+
+    // Operands are read a phase ahead of the MFMAs that take them; the vector work of a 32-row
+    // block sits next to the matrix work of the other one.
+    bf16x8 ar[KS], at[CB][2], pop0[2], ds0[2], pop1[2], ds1[2];
+    f32x16 s0, p0, s1, p1;
+    f32x4 l4[4], d4[4];
+    auto product = [&](const bf16x8 (&b)[KS], f32x16& acc) {
+      zero(acc);
 #pragma unroll
-    for (int qb = 0; qb < kBwdStream / 32; ++qb) {
-      f32x16 sacc, dpacc;
-      zero(sacc);
-      zero(dpacc);
-#pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        sacc = mfma(read_rows<D>(q_lds, 32 * qb + lq, s, hh), kop[s], sacc);
-        dpacc = mfma(read_rows<D>(do_lds, 32 * qb + lq, s, hh), vop[s], dpacc);
-      }
-      bf16x8 pop[2], dsop[2];
+      for (int s = 0; s < KS; ++s) acc = mfma(ar[s], b[s], acc);
+    };
+    auto read_stats = [&](int qb) {
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const int rb = 32 * qb + 8 * i4 + 4 * hh;   // four consecutive rows
-        const f32x4 l4 = *(const f32x4*)&lse_lds[rb], d4 = *(const f32x4*)&dl_lds[rb];
+        l4[i4] = *(const f32x4*)&lse_lds[32 * qb + 8 * i4 + 4 * hh];
+        d4[i4] = *(const f32x4*)&dl_lds[32 * qb + 8 * i4 + 4 * hh];
+      }
+    };
+    auto p_ds_operands = [&](const f32x16& sacc, const f32x16& dpacc, int qb, bf16x8 (&pop)[2], bf16x8 (&dsop)[2]) {
+      float pv[16];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * i4 + e;
-          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -l4[e]));
-          if (masked) {
-            const int qi = i0 + rb + e;
-            if (!(valid && qi < N && !(causal && key > qi + shift))) p = 0.0f;
-          }
-          pop[i >> 3][i & 7] = (bf16)p;
-          dsop[i >> 3][i & 7] = (bf16)(p * (dpacc[i] - d4[e]));
+      for (int i = 0; i < 16; ++i) pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -l4[i >> 2][i & 3]));
+      if (masked) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int qi = i0 + 32 * qb + acc_row(i, hh);
+          const bool vis = valid && qi < N && !(causal && key > qi + shift);
+          pv[i] = vis ? pv[i] : 0.0f;
         }
       }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        pop[i >> 3][i & 7] = (bf16)pv[i];
+        dsop[i >> 3][i & 7] = (bf16)(pv[i] * (dpacc[i] - d4[i >> 2][i & 3]));
+      }
+    };
+    auto update = [&](const bf16x8 (&b)[2], f32x16 (&acc)[CB]) {
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          dvacc[cb] = mfma(read_transposed<D>(do_lds, 32 * qb + 16 * tt, cb, lane), pop[tt], dvacc[cb]);
-          dkacc[cb] = mfma(read_transposed<D>(q_lds, 32 * qb + 16 * tt, cb, lane), dsop[tt], dkacc[cb]);
-        }
-    }
+        for (int tt = 0; tt < 2; ++tt) acc[cb] = mfma(at[cb][tt], b[tt], acc[cb]);
+    };
+    read_rows<D>(q_lds, 0, off, ar);
+    fence();
+    product(kop, s0);
+    read_rows<D>(do_lds, 0, off, ar);
+    fence();
+    product(vop, p0);
+    read_rows<D>(q_lds, 1, off, ar);
+    read_stats(0);
+    fence();
+    product(kop, s1);
+    read_rows<D>(do_lds, 1, off, ar);
+    fence();
+    product(vop, p1);
+    p_ds_operands(s0, p0, 0, pop0, ds0);
+    read_transposed<D>(do_lds, 0, off, at);
+    fence();
+    update(pop0, dvacc);
+    read_transposed<D>(q_lds, 0, off, at);
+    read_stats(1);
+    fence();
+    update(ds0, dkacc);
+    p_ds_operands(s1, p1, 1, pop1, ds1);
+    read_transposed<D>(do_lds, 1, off, at);
+    fence();
+    update(pop1, dvacc);
+    read_transposed<D>(q_lds, 1, off, at);
+    fence();
+    update(ds1, dkacc);
+  };
+  for (int it = 0; it < n_it; it += 2) {
+    tile_step(std::integral_constant<int, 0>(), it);
+    if (it + 1 < n_it) tile_step(std::integral_constant<int, 1>(), it + 1);
   }
   if (valid) {
     bf16* dkrow = dk + (bk * Nk + key) * D;
