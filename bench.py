@@ -68,6 +68,7 @@ def main():
     ap.add_argument("--workload", default="long", help="headline configuration (workloads.CONFIGS)")
     ap.add_argument("--only", action="store_true", help="measure the headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--backward", action="store_true", help="also time the backward pass on the headline workload")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device-to-device copy of MIB mebibytes (5 times): the known-size "
                          "kernel against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -266,6 +267,31 @@ def main():
         out["backward_exact"] = {"ms": ms, "alu_frac": 4.0 * fl_e / (ms * 1e-3) / 1e12 / PEAK_FP32_TFLOPS}
         return out
 
+    def backward_table(cfg, tensors, steps):
+        """The backward pass for bf16 tensors on the matrix cores (gradient with the grouping held
+        fixed), DistrAttention and exact: three launches (prepare, dQ, dK/dV); the two main kernels
+        execute seven products of d multiply-adds per visible (query, key) pair."""
+        q, k, v = tensors
+        dout = to_dev(W.make_grad(cfg), cfg.dtype)
+        o = torch.empty_like(q)
+        lse = torch.empty((cfg.B, cfg.H, cfg.N), dtype=torch.float32, device=dev)
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(k)
+        common = dict(Br=cfg.Br, Bc=cfg.Bc, causal=cfg.causal, n_planes=cfg.n_planes, lsh_seed=cfg.lsh_seed, lse_out=lse)
+        flops = 14.0 * cfg.d * cfg.B * cfg.H * visible_pairs(cfg.N, cfg.causal)
+        out = {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} Hkv={cfg.Hkv} N={cfg.N} d={cfg.d} bf16 "
+                           f"{'causal' if cfg.causal else 'non-causal'} Br={cfg.Br} n_groups={cfg.n_groups}",
+               "executed_flops": flops}
+        for name, fwd, bwd, p in (
+                ("distr", da.distr_attn_fwd_ex, da.distr_attn_bwd_ex, da.make_params(q, k, v, n_groups=cfg.n_groups, **common)),
+                ("exact", da.distr_attn_exact_fwd_ex, da.distr_attn_exact_bwd_ex, da.make_params(q, k, v, **common))):
+            fwd(q, k, v, o, p)
+            run = lambda: bwd(q, k, v, o, dout, lse, dq, dk, dv, p)
+            run()
+            ms_f = ev_time(lambda: fwd(q, k, v, o, p), steps)
+            ms = ev_time(run, steps)
+            out[name] = {"ms": ms, "ms_forward": ms_f, "mfma_frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        return out
+
     results = {}
     head_cfg = W.CONFIGS[args.workload]
     order = [args.workload] if args.only else [n for n in ("vit", "llama", "mid", "long", "tiny")]
@@ -292,6 +318,11 @@ def main():
             t = results[f"block_sizes_d{cfg.d}"]
             log(f"[bench] block sizes d={cfg.d}: best distr {t['best_distr']}, best exact {t['best_exact']}, "
                 f"rule {t['rule_pick']}")
+        if (args.backward and name == args.workload) or (not args.only and name in ("llama", "mid")):
+            results[f"backward_{name}"] = backward_table(cfg, tensors, max(3, args.steps // 4))
+            t = results[f"backward_{name}"]
+            log(f"[bench] backward {name}: distr {t['distr']['ms']:.3f} ms, exact {t['exact']['ms']:.3f} ms, "
+                f"{t['distr']['mfma_frac']:.3f} / {t['exact']['mfma_frac']:.3f} of the bf16 peak in executed FLOPs")
         if name == args.workload:
             head_inputs = host
         del tensors

@@ -213,7 +213,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_prepare_kernel(
 
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kBwdThreads, (D == 128 ? 1 : 2)) void bwd_dq_kernel(
+__global__ __launch_bounds__(kBwdThreads, 2) void bwd_dq_kernel(
     const bf16* __restrict__ qrep, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ dout, const float* __restrict__ lse2p, const float* __restrict__ delta,
     bf16* __restrict__ dq, const uint8_t* __restrict__ perm, int H, int Hkv, int N, int Nk, int Br, int Tq,
@@ -250,6 +250,7 @@ __global__ __launch_bounds__(kBwdThreads, (D == 128 ? 1 : 2)) void bwd_dq_kernel
   const __amdgpu_buffer_rsrc_t v_rsrc = head_rsrc(v + (size_t)(b * Hkv + hk) * Nk * D, head_bytes);
   const TileLoader<D> loader(w, lane);
   const int n_end = causal ? min(Nk, r0 + rows + shift) : Nk;
+  const int n_tiles = ((n_end + kBwdStream - 1) / kBwdStream + 1) & ~1;   // even
   // tiles that end at or before n_free need no mask for any row of the workgroup
   const int n_free = causal ? min(r0 + shift + 1, Nk) : Nk;
   loader.load(k_rsrc, 0, k_lds0);
@@ -276,21 +277,12 @@ __global__ __launch_bounds__(kBwdThreads, (D == 128 ? 1 : 2)) void bwd_dq_kernel
   for (int cb = 0; cb < CB; ++cb) zero(dqacc[cb]);
 
   const OperandOffsets<D> off(lane);
-  // one 32-key block: S^T and dP^T from the operands already read, then dS^T as B operands
-  auto scores = [&](const bf16x8 (&ak)[KS], const bf16x8 (&av)[KS], f32x16& sacc, f32x16& dpacc) {
-    zero(sacc);
-    zero(dpacc);
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      sacc = mfma(ak[s], qop[s], sacc);
-      dpacc = mfma(av[s], doop[s], dpacc);
-    }
-  };
-  auto ds_operands = [&](const f32x16& sacc, const f32x16& dpacc, int kv0, bool masked, bf16x8 (&dsop)[2]) {
+  // dS^T of one 32-key block as B operands
+  auto ds_operands = [&](const f32x16& sacc, const f32x16& dpacc, int kv0, auto masked_c, bf16x8 (&dsop)[2]) {
     float pv[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -lse2));
-    if (masked) {
+    if constexpr (decltype(masked_c)::value) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) pv[i] = kv0 + acc_row(i, hh) <= lim ? pv[i] : 0.0f;
     }
@@ -305,52 +297,66 @@ __global__ __launch_bounds__(kBwdThreads, (D == 128 ? 1 : 2)) void bwd_dq_kernel
   };
 
   // One tile; the loop is unrolled by two so that every buffer is a fixed object in each copy
-  // (the compiler then knows that the loads in flight do not touch the tile being read).
-  auto tile_step = [&](auto par_c, int n0) {
+  // (the compiler then knows that the loads in flight do not touch the tile being read). Tiles
+  // that need the mask take a copy of their own: a branch inside the body would end the region
+  // in which the vector work is scheduled between the MFMAs.
+  auto tile_step = [&](auto par_c, auto masked, int n0) __attribute__((always_inline)) {
     constexpr int par = decltype(par_c)::value;
     const char* k_lds = par ? k_lds1 : k_lds0;
     const char* v_lds = par ? v_lds1 : v_lds0;
-    if constexpr (D == 128) {
-      // Register classes, stated once per tile (one wave per SIMD, both halves of the register
-      // file in use): the dQ~ accumulators live in the accumulator half, the resident Q~ and dO
-      // operands in the vector half.
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb) asm volatile("" : "+a"(dqacc[cb]));
-#pragma unroll
-      for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qop[s]), "+v"(doop[s]));
-    }
     wait_loads();
     __syncthreads();   // this tile has landed; the other buffers' readers are done
-    if (n0 + kBwdStream < n_end) {
+    if (n0 + kBwdStream < n_tiles * kBwdStream) {
       loader.load(k_rsrc, n0 + kBwdStream, par ? k_lds0 : k_lds1);
       loader.load(v_rsrc, n0 + kBwdStream, par ? v_lds0 : v_lds1);
     }
-    const bool masked = n0 + kBwdStream > n_free;
-    // Operands are read a phase ahead of the MFMAs that take them; the vector work of a block
-    // sits next to the matrix work of the other one.
-    bf16x8 ak[KS], av[KS], at[CB][2], ds0[2], ds1[2];
-    f32x16 s0, p0, s1, p1;
-    read_rows<D>(k_lds, 0, off, ak);
-    read_rows<D>(v_lds, 0, off, av);
-    fence();
-    scores(ak, av, s0, p0);
-    read_rows<D>(k_lds, 1, off, ak);
-    read_rows<D>(v_lds, 1, off, av);
-    fence();
-    scores(ak, av, s1, p1);
-    ds_operands(s0, p0, n0, masked, ds0);
-    read_transposed<D>(k_lds, 0, off, at);
-    fence();
-    dq_update(at, ds0);
-    ds_operands(s1, p1, n0 + 32, masked, ds1);
-    read_transposed<D>(k_lds, 1, off, at);
-    fence();
-    dq_update(at, ds1);
+    // Two waves share a SIMD (a single wave cannot fill it: its LDS reads alone take as many
+    // issue cycles as its MFMAs take pipe cycles), so the blocks follow one another and operands
+    // are read in batches of HB contraction steps in front of their MFMAs (all of them at d = 64;
+    // at d = 128 two batches: with the 96 accumulator registers the whole set does not fit beside
+    // the resident operands).
+    constexpr int HB = D == 128 ? KS / 2 : KS;
+#pragma unroll
+    for (int mb = 0; mb < kBwdStream / 32; ++mb) {
+      bf16x8 ak[HB], av[HB], at[CB][2], ds[2];
+      f32x16 sacc, dpacc;
+      zero(sacc);
+      zero(dpacc);
+#pragma unroll
+      for (int h0 = 0; h0 < KS; h0 += HB) {
+#pragma unroll
+        for (int s = 0; s < HB; ++s) {
+          ak[s] = *(const bf16x8*)(k_lds + mb * 32 * (D * 2) + off.rows[h0 + s]);
+          av[s] = *(const bf16x8*)(v_lds + mb * 32 * (D * 2) + off.rows[h0 + s]);
+        }
+        fence();
+#pragma unroll
+        for (int s = 0; s < HB; ++s) {
+          sacc = mfma(ak[s], qop[h0 + s], sacc);
+          dpacc = mfma(av[s], doop[h0 + s], dpacc);
+        }
+        fence();
+      }
+      ds_operands(sacc, dpacc, n0 + 32 * mb, masked, ds);
+      read_transposed<D>(k_lds, mb, off, at);
+      fence();
+      dq_update(at, ds);
+      fence();
+    }
   };
-  for (int n0 = 0; n0 < n_end; n0 += 2 * kBwdStream) {
-    tile_step(std::integral_constant<int, 0>(), n0);
-    if (n0 + kBwdStream < n_end) tile_step(std::integral_constant<int, 1>(), n0 + kBwdStream);
-  }
+  // Tiles [a, b), b - a even, with or without the mask; buffer parity = tile parity. The loop is
+  // unrolled by two over fixed buffers; masked and unmasked tiles run in loops of their own (both
+  // copies under a branch inside one loop cost 200 spilled registers). The tile count is rounded
+  // up to an even number: a tile past the last visible key is masked out entirely.
+  auto run = [&](int a, int b, auto masked_c) {
+    for (int t = a; t < b; t += 2) {
+      tile_step(std::integral_constant<int, 0>(), masked_c, t * kBwdStream);
+      tile_step(std::integral_constant<int, 1>(), masked_c, (t + 1) * kBwdStream);
+    }
+  };
+  const int free_tiles = min(n_free / kBwdStream, n_tiles) & ~1;
+  run(0, free_tiles, std::false_type());
+  run(free_tiles, n_tiles, std::true_type());
 
   // Epilogue: every wave puts the dQ~ of its 32 rows into LDS (float; the column index XORed
   // with the row so that a register's 32 rows fall into different banks) and sums, for every
@@ -448,7 +454,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
 
   // causal: query i sees key n iff n <= i + shift; the first tile with a row that sees key n0
   const int i_start = causal ? max(0, n0 - shift) / kBwdStream * kBwdStream : 0;
-  const int tiles = (N - i_start + kBwdStream - 1) / kBwdStream;   // per query head
+  const int tiles = ((N - i_start + kBwdStream - 1) / kBwdStream + 1) & ~1;   // per query head, even
   const int n_it = rep * tiles;
   const TileLoader<D> loader(w, lane);
   const QueryStream<D> ctx = {qrep, dout, lse2p, delta, (size_t)b * H + hk * rep, N, i_start, tiles, w, lane, loader};
@@ -478,7 +484,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
   const OperandOffsets<D> off(lane);
   // One tile; the loop is unrolled by two so that every buffer is a fixed object in each copy
   // (the compiler then knows that the loads in flight do not touch the tile being read).
-  auto tile_step = [&](auto par_c, int it) {
+  auto tile_step = [&](auto par_c, auto masked_c, int it) __attribute__((always_inline)) {
     constexpr int par = decltype(par_c)::value;
     const char* q_lds = par ? q_lds1 : q_lds0;
     const char* do_lds = par ? do_lds1 : do_lds0;
@@ -498,9 +504,6 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
       if constexpr (par) ctx.issue(it + 1, q_lds0, do_lds0, lse_lds0, dl_lds0);
       else ctx.issue(it + 1, q_lds1, do_lds1, lse_lds1, dl_lds1);
     }
-    // no mask: every row is a query, every key of the workgroup exists and is visible to all rows
-    const bool masked = i0 + kBwdStream > N || n0 + kBwdRows > Nk || (causal && n0 + kBwdRows - 1 > i0 + shift);
-
     // Operands are read a phase ahead of the MFMAs that take them; the vector work of a 32-row
     // block sits next to the matrix work of the other one.
     bf16x8 ar[KS], at[CB][2], pop0[2], ds0[2], pop1[2], ds1[2];
@@ -522,7 +525,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
       float pv[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i) pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], sl2e, -l4[i >> 2][i & 3]));
-      if (masked) {
+      if constexpr (decltype(masked_c)::value) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int qi = i0 + 32 * qb + acc_row(i, hh);
@@ -571,9 +574,28 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
     fence();
     update(ds1, dkacc);
   };
-  for (int it = 0; it < n_it; it += 2) {
-    tile_step(std::integral_constant<int, 0>(), it);
-    if (it + 1 < n_it) tile_step(std::integral_constant<int, 1>(), it + 1);
+  // Iterations [a, b), b - a even, with or without the mask; buffer parity = iteration parity.
+  // The loop is unrolled by two over fixed buffers, masked and unmasked tiles run in loops of
+  // their own.
+  auto run = [&](int a, int b, auto masked_c) {
+    for (int it = a; it < b; it += 2) {
+      tile_step(std::integral_constant<int, 0>(), masked_c, it);
+      tile_step(std::integral_constant<int, 1>(), masked_c, it + 1);
+    }
+  };
+  // Per query head (an even number of tiles; a tile past the last query row is masked out
+  // entirely): the first m1 tiles touch the causal diagonal (all tiles, when some key of the
+  // workgroup does not exist), the last two may hold rows past N; the tiles between need no
+  // mask: every row is a query, every key exists and is visible to all rows.
+  int m1 = 0;
+  if (n0 + kBwdRows > Nk) m1 = tiles;
+  else if (causal) m1 = min(tiles, (max(0, (n0 + kBwdRows - 1 - shift - i_start + kBwdStream - 1) / kBwdStream) + 1) & ~1);
+  const int m2 = (i_start + tiles * kBwdStream > N && m1 < tiles) ? 2 : 0;
+  for (int hh_ = 0; hh_ < rep; ++hh_) {
+    const int base = hh_ * tiles;
+    run(base, base + m1, std::true_type());
+    run(base + m1, base + tiles - m2, std::false_type());
+    run(base + tiles - m2, base + tiles, std::true_type());
   }
   if (valid) {
     bf16* dkrow = dk + (bk * Nk + key) * D;
