@@ -174,6 +174,45 @@ def test_structure_of_the_gradient():
     assert np.abs(dv[0, 0] - P.T @ do[0, 0].astype(np.float64)).max() < 1e-13
 
 
+@pytest.mark.parametrize("kw", CASES)
+def test_distr_backward_is_the_exact_backward_on_the_replicated_queries(kw):
+    """S^ = Q_r K_f^T = Q~ K^T with Q~ = Q whose every channel is replaced by the sampled channel
+    of its group (a sum over groups of sums over members): the gradient with the grouping held
+    fixed is the exact-attention gradient taken at Q~, with dQ~ summed over each group's members
+    into the sampled channel. The matrix-core kernels compute it that way; here the two oracle
+    functions are held against each other."""
+    q, k, v, do, p = problem(21, **kw)
+    _, perm, _ = oracle.lsh_group(q, p)
+    G = p.d // p.n_groups
+    q_rep = np.empty_like(q)
+    Tq = (p.N + p.Br - 1) // p.Br
+    for b in range(p.B):
+        for h in range(p.H):
+            for t in range(Tq):
+                rows = slice(t * p.Br, min(p.N, (t + 1) * p.Br))
+                pm = perm[b, h, t].astype(int)
+                for j in range(p.n_groups):
+                    for c in pm[j * G:(j + 1) * G]:
+                        q_rep[b, h, rows, c] = q[b, h, rows, pm[j * G]]
+    p_exact = oracle.params(p.B, p.H, p.Hkv, p.N, p.d, p.Br, p.d, causal=bool(p.causal), scale=p.scale,
+                            Nk=p.Nk if p.Nk > 0 else None)
+    assert np.abs(oracle.exact_fwd(q_rep, k, v, p_exact) - oracle.distr_fwd(q, k, v, p)).max() < 1e-12
+    dq_rep, dk_e, dv_e = oracle.exact_bwd(q_rep, k, v, do, p_exact)
+    dq, dk, dv = oracle.distr_bwd(q, k, v, do, p)
+    dq_sum = np.zeros_like(dq)
+    for b in range(p.B):
+        for h in range(p.H):
+            for t in range(Tq):
+                rows = slice(t * p.Br, min(p.N, (t + 1) * p.Br))
+                pm = perm[b, h, t].astype(int)
+                for j in range(p.n_groups):
+                    dq_sum[b, h, rows, pm[j * G]] = dq_rep[b, h, rows][:, pm[j * G:(j + 1) * G]].sum(-1)
+    unit = max(1.0, np.abs(dq).max(), np.abs(dk).max())
+    assert np.abs(dq_sum - dq).max() < 1e-12 * unit
+    assert np.abs(dk_e - dk).max() < 1e-12 * unit
+    assert np.abs(dv_e - dv).max() < 1e-12 * unit
+
+
 @pytest.mark.parametrize("kw", [dict(), dict(causal=True, N=20, Nk=29), dict(H=4, Hkv=2, causal=True)])
 def test_row_statistics(kw):
     q, k, v, do, p = problem(9, **kw)
