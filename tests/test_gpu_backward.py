@@ -99,6 +99,8 @@ BF16_CASES = [
     ("mid", dict(B=1, H=2, Hkv=1, N=200, n_groups=16)),         # groups of eight channels
     ("vit", dict(B=1, H=2, Hkv=2, N=129, n_groups=64)),         # one channel per group
     ("vit", dict(B=1, H=2, Hkv=1, N=1, Nk=70)),                 # a single query row
+    ("llama", dict(H=4, Hkv=1, N=4096)),                        # the full sequence length of "llama", one kv head
+    ("mid", dict(B=1, H=2, Hkv=2, N=2048)),                     # 32 tiles per workgroup at d = 128
 ]
 
 
