@@ -177,3 +177,52 @@ def test_backward_refuses_the_mirrored_form():
     with pytest.raises(da.DistrAttnError) as e:
         da.distr_attn_bwd_ex(x, x, x, outs[0], outs[1], lse, outs[2], outs[3], outs[4], p)
     assert e.value.code == da.DA_ERR_UNSUPPORTED
+
+
+def test_forward_and_backward_replay_from_a_hip_graph():
+    """With caller-provided workspaces a training step's attention (forward with row statistics,
+    then the backward) is launches only, so it can be captured once and replayed: every replay,
+    with eager work and synchronisations in between, must equal the eager result on the inputs of
+    that moment."""
+    import torch
+
+    import gpu_util as U
+    import paper_2507_17245_amd as da
+    cfg = W.CONFIGS["llama"].scaled(H=4, Hkv=2, N=333)
+    q, k, v = W.make(cfg)
+    tq, tk, tv, tdo = (U.to_dev(x, "bf16") for x in (q, k, v, W.make_grad(cfg)))
+    common = dict(Br=cfg.Br, n_groups=cfg.n_groups, causal=cfg.causal, lsh_seed=cfg.lsh_seed)
+    probe = da.make_params(tq, tk, tv, **common)
+    bytes_f, bytes_b = da.distr_attn_workspace_bytes(probe), da.distr_attn_bwd_workspace_bytes(probe)
+
+    def buffers():
+        return dict(o=torch.empty_like(tq), lse=torch.empty((cfg.B, cfg.H, cfg.N), dtype=torch.float32, device="cuda"),
+                    dq=torch.empty_like(tq), dk=torch.empty_like(tk), dv=torch.empty_like(tk),
+                    wf=torch.empty(bytes_f, dtype=torch.uint8, device="cuda"),
+                    wb=torch.empty(bytes_b, dtype=torch.uint8, device="cuda"))
+
+    def step(x):
+        da.distr_attn_fwd_ex(tq, tk, tv, x["o"], da.make_params(tq, tk, tv, workspace=x["wf"], lse_out=x["lse"], **common))
+        da.distr_attn_bwd_ex(tq, tk, tv, x["o"], tdo, x["lse"], x["dq"], x["dk"], x["dv"],
+                             da.make_params(tq, tk, tv, workspace=x["wb"], **common))
+
+    g, e = buffers(), buffers()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        step(g)
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    for rep in range(4):
+        if rep:   # new inputs in the captured buffers
+            for t in (tq, tk, tv, tdo):
+                t.copy_(torch.randn(t.shape, device="cuda", generator=gen).to(torch.bfloat16))
+        for name in ("dq", "dk", "dv"):
+            g[name].fill_(float("nan"))
+        step(e)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in ("o", "dq", "dk", "dv"):
+            assert torch.equal(g[name].view(torch.int16), e[name].view(torch.int16)), (name, rep)
