@@ -101,6 +101,7 @@ BF16_CASES = [
     ("vit", dict(B=1, H=2, Hkv=1, N=1, Nk=70)),                 # a single query row
     ("llama", dict(H=4, Hkv=1, N=4096)),                        # the full sequence length of "llama", one kv head
     ("mid", dict(B=1, H=2, Hkv=2, N=2048)),                     # 32 tiles per workgroup at d = 128
+    ("long", dict(B=2, H=4, Hkv=2, N=150, Nk=290)),             # batch x grouped heads x more keys, causal
 ]
 
 
