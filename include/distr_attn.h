@@ -147,7 +147,8 @@ int distr_attn_exact_bwd_ex(const void *q, const void *k, const void *v, const v
                             const da_params *p);
 
 /* Bytes of p->workspace the backward calls need at most for p (0 for invalid parameters):
- * the grouping table and, for bf16 tensors, 4 bytes per query row plus a copy of q. */
+ * the grouping table and, for bf16 tensors, 8 bytes per query row, a copy of q and (grouped-query
+ * shapes with few kv heads) float partial sums of dk and dv per query head of a kv head. */
 size_t distr_attn_bwd_workspace_bytes(const da_params *p);
 
 /*

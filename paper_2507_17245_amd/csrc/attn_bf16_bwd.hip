@@ -427,7 +427,8 @@ template <int D>
 __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
     const bf16* __restrict__ qrep, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ dout, const float* __restrict__ lse2p, const float* __restrict__ delta,
-    bf16* __restrict__ dk, bf16* __restrict__ dv, int H, int Hkv, int N, int Nk, int Tw, int causal, float scale) {
+    bf16* __restrict__ dk, bf16* __restrict__ dv, float* __restrict__ part, int hsplit, int H, int Hkv, int N,
+    int Nk, int Tw, int causal, float scale) {
   constexpr int KS = D / 16;
   constexpr int CB = D / 32;
   constexpr int TILE = kBwdStream * D * 2;
@@ -442,10 +443,13 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int lq = lane & 31, hh = lane >> 5;
-  const int t = blockIdx.x % Tw;
-  const size_t bk = blockIdx.x / Tw;   // b * Hkv + hk
+  // hsplit > 1: the query heads of the kv head are dealt out to hsplit workgroups, which leave
+  // float partial sums in `part` for the reduction kernel
+  const int hs = blockIdx.x % hsplit;
+  const int t = (blockIdx.x / hsplit) % Tw;
+  const size_t bk = blockIdx.x / hsplit / Tw;   // b * Hkv + hk
   const int b = (int)(bk / Hkv), hk = (int)(bk % Hkv);
-  const int rep = H / Hkv;
+  const int rep = H / Hkv / hsplit;             // query heads of this workgroup
   const int n0 = t * kBwdRows;
   const int key = n0 + 32 * w + lq;
   const bool valid = key < Nk;
@@ -457,7 +461,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
   const int tiles = ((N - i_start + kBwdStream - 1) / kBwdStream + 1) & ~1;   // per query head, even
   const int n_it = rep * tiles;
   const TileLoader<D> loader(w, lane);
-  const QueryStream<D> ctx = {qrep, dout, lse2p, delta, (size_t)b * H + hk * rep, N, i_start, tiles, w, lane, loader};
+  const QueryStream<D> ctx = {qrep, dout, lse2p, delta, (size_t)b * H + (hk * hsplit + hs) * rep, N, i_start, tiles, w, lane, loader};
   ctx.issue(0, q_lds0, do_lds0, lse_lds0, dl_lds0);
 
   bf16x8 kop[KS], vop[KS];
@@ -597,7 +601,26 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
     run(base + m1, base + tiles - m2, std::false_type());
     run(base + tiles - m2, base + tiles, std::true_type());
   }
-  if (valid) {
+  if (valid && hsplit > 1) {
+    // partial sums: [dK | dV][hsplit][B * Hkv * Nk][D] float
+    const size_t elems = (size_t)gridDim.x / hsplit / Tw * Nk * D;
+    float* dkrow = part + (size_t)hs * elems + (bk * Nk + key) * D;
+    float* dvrow = dkrow + (size_t)hsplit * elems;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int c = 32 * cb + 8 * i4 + 4 * hh;
+        f32x4 a, bq;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          a[e] = scale * dkacc[cb][4 * i4 + e];
+          bq[e] = dvacc[cb][4 * i4 + e];
+        }
+        *(f32x4*)(dkrow + c) = a;
+        *(f32x4*)(dvrow + c) = bq;
+      }
+  } else if (valid) {
     bf16* dkrow = dk + (bk * Nk + key) * D;
     bf16* dvrow = dv + (bk * Nk + key) * D;
 #pragma unroll
@@ -617,10 +640,36 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
   }
 }
 
+// dK and dV from the partial sums of the head-split dK/dV launch: out = sum over the hsplit parts,
+// in a fixed order (results do not depend on the run), rounded once.
+__global__ __launch_bounds__(256) void bwd_reduce_kernel(const float* __restrict__ part, bf16* __restrict__ dk,
+                                                         bf16* __restrict__ dv, size_t elems, int hsplit) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= 2 * elems) return;
+  const bool second = i >= elems;
+  const size_t j = second ? i - elems : i;
+  const float* src = part + (second ? (size_t)hsplit * elems : 0) + j;
+  f32x4 acc = *(const f32x4*)src;
+  for (int s = 1; s < hsplit; ++s) acc += *(const f32x4*)(src + (size_t)s * elems);
+  bf16x4 y = {(bf16)acc[0], (bf16)acc[1], (bf16)acc[2], (bf16)acc[3]};
+  *(bf16x4*)((second ? dv : dk) + j) = y;
+}
+
+// Workgroups of the dK/dV launch that share one kv head's keys but take different query heads: used
+// when the launch would otherwise not fill the chip twice over (grouped-query shapes with few kv
+// heads; under the causal mask its workgroups differ many-fold in length and need company).
+static int dkv_head_split(const Problem& pb) {
+  const int rep = pb.H / pb.Hkv;
+  const long long k_units = (long long)pb.B * pb.Hkv * ((pb.Nk + kBwdRows - 1) / kBwdRows);
+  return (rep > 1 && k_units < 512) ? rep : 1;
+}
+
 size_t attn_bf16_bwd_scratch_bytes(const Problem& pb, int distr) {
   const size_t rows = (size_t)pb.B * pb.H * pb.N;
   const size_t stat = (rows * 4 + 255) & ~(size_t)255;   // D_i, and lse * log2(e)
-  return 2 * stat + (distr ? ((rows * pb.d * 2 + 255) & ~(size_t)255) : 0);
+  const int hsplit = dkv_head_split(pb);
+  const size_t part = hsplit > 1 ? ((size_t)2 * hsplit * pb.B * pb.Hkv * pb.Nk * pb.d * 4 + 255) & ~(size_t)255 : 0;
+  return 2 * stat + (distr ? ((rows * pb.d * 2 + 255) & ~(size_t)255) : 0) + part;
 }
 
 hipError_t launch_attn_bf16_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
@@ -632,7 +681,7 @@ hipError_t launch_attn_bf16_bwd(const void* q, const void* k, const void* v, con
   const long long prep_units = (long long)pb.B * pb.H * Tq;
   const long long q_units = (long long)pb.B * pb.H * Twq;
   const long long k_units = (long long)pb.B * pb.Hkv * Twk;
-  if (prep_units > 0x7fffffffLL || q_units > 0x7fffffffLL || k_units > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (prep_units > 0x7fffffffLL || q_units > 0x7fffffffLL || k_units > 0x7fffffffLL / 16) return hipErrorInvalidValue;
   if ((pb.d != 64 && pb.d != 128) || pb.Br % 32 != 0 || pb.d % pb.n_groups != 0) return hipErrorInvalidValue;
   // tiles are addressed by 32-bit byte offsets inside a head
   if ((size_t)pb.N * pb.d * 2 >= 0x7fffffffULL || (size_t)pb.Nk * pb.d * 2 >= 0x7fffffffULL) return hipErrorInvalidValue;
@@ -641,6 +690,9 @@ hipError_t launch_attn_bf16_bwd(const void* q, const void* k, const void* v, con
   float* delta = (float*)scratch;
   float* lse2 = (float*)((char*)scratch + stat);
   bf16* qrep = distr ? (bf16*)((char*)scratch + 2 * stat) : nullptr;
+  const int hsplit = dkv_head_split(pb);
+  float* part = hsplit > 1 ? (float*)((char*)scratch + 2 * stat + (distr ? ((rows * pb.d * 2 + 255) & ~(size_t)255) : 0)) : nullptr;
+  const size_t kv_elems = (size_t)pb.B * pb.Hkv * pb.Nk * pb.d;
   const uint8_t* table = distr ? perm : nullptr;
   const bf16* qx = distr ? qrep : (const bf16*)q;
   const int n_groups = distr ? pb.n_groups : pb.d;
@@ -651,9 +703,12 @@ hipError_t launch_attn_bf16_bwd(const void* q, const void* k, const void* v, con
     hipLaunchKernelGGL((bwd_dq_kernel<DD>), dim3((unsigned)q_units), dim3(kBwdThreads), 0, stream, qx, (const bf16*)k, \
                        (const bf16*)v, (const bf16*)dout, lse2, delta, (bf16*)dq, table, pb.H, pb.Hkv, pb.N, pb.Nk,   \
                        pb.Br, Tq, Twq, n_groups, pb.causal, pb.scale);                                               \
-    hipLaunchKernelGGL((bwd_dkv_kernel<DD>), dim3((unsigned)k_units), dim3(kBwdThreads), 0, stream, qx,              \
-                       (const bf16*)k, (const bf16*)v, (const bf16*)dout, lse2, delta, (bf16*)dk, (bf16*)dv, pb.H,    \
-                       pb.Hkv, pb.N, pb.Nk, Twk, pb.causal, pb.scale);                                               \
+    hipLaunchKernelGGL((bwd_dkv_kernel<DD>), dim3((unsigned)(k_units * hsplit)), dim3(kBwdThreads), 0, stream, qx,   \
+                       (const bf16*)k, (const bf16*)v, (const bf16*)dout, lse2, delta, (bf16*)dk, (bf16*)dv, part,    \
+                       hsplit, pb.H, pb.Hkv, pb.N, pb.Nk, Twk, pb.causal, pb.scale);                                 \
+    if (hsplit > 1)                                                                                                  \
+      hipLaunchKernelGGL(bwd_reduce_kernel, dim3((unsigned)((2 * kv_elems / 4 + 255) / 256)), dim3(256), 0, stream,  \
+                         part, (bf16*)dk, (bf16*)dv, kv_elems, hsplit);                                              \
   } while (0)
   if (pb.d == 64) DA_BWD(64);
   else DA_BWD(128);
