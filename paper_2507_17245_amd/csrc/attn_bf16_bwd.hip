@@ -424,7 +424,7 @@ struct QueryStream {
 
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
+__global__ __launch_bounds__(kBwdThreads, (D == 64 ? 2 : 1)) void bwd_dkv_kernel(
     const bf16* __restrict__ qrep, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ dout, const float* __restrict__ lse2p, const float* __restrict__ delta,
     bf16* __restrict__ dk, bf16* __restrict__ dv, float* __restrict__ part, int hsplit, int H, int Hkv, int N,
@@ -498,10 +498,12 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_dkv_kernel(
     // Register classes, stated once per tile: the accumulators of dK and dV live in the
     // accumulator half of the register file, the resident K and V operands in the vector half
     // (left to itself the allocator moved 128 accumulator registers back and forth per tile).
+    if constexpr (D == 128) {
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) asm volatile("" : "+a"(dkacc[cb]), "+a"(dvacc[cb]));
+      for (int cb = 0; cb < CB; ++cb) asm volatile("" : "+a"(dkacc[cb]), "+a"(dvacc[cb]));
 #pragma unroll
-    for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(kop[s]), "+v"(vop[s]));
+      for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(kop[s]), "+v"(vop[s]));
+    }
     wait_loads();
     __syncthreads();   // this tile has landed; the other buffers' readers are done
     if (it + 1 < n_it) {
