@@ -111,6 +111,22 @@ def test_workspace_bytes():
     assert da.distr_attn_workspace_bytes(_params(n_groups=7)) == 0
 
 
+def test_backward_workspace_bytes():
+    """Table + 8 bytes per query row + a copy of q; grouped-query shapes whose dK/dV launch is
+    split over the query heads add float partial sums of dk and dv per query head of a kv head;
+    float tensors need the table only."""
+    al = lambda n: (n + 255) // 256 * 256
+    B, H, N, d, Br = 2, 4, 197, 64, 64
+    table = al(B * H * ((N + Br - 1) // Br) * d)
+    rows = B * H * N
+    mha = da.distr_attn_bwd_workspace_bytes(_params(B=B, H=H, Hkv=H, N=N, d=d, Br=Br))
+    assert mha == table + 2 * al(rows * 4) + al(rows * d * 2)
+    gqa = da.distr_attn_bwd_workspace_bytes(_params(B=B, H=H, Hkv=2, N=N, d=d, Br=Br))
+    assert gqa == mha + al(2 * (H // 2) * B * 2 * N * d * 4)
+    assert da.distr_attn_bwd_workspace_bytes(_params(B=B, H=H, Hkv=H, N=N, d=d, Br=Br, dtype=da.DA_F32)) == table
+    assert da.distr_attn_bwd_workspace_bytes(_params(n_groups=7)) == 0
+
+
 def test_bench_refuses_more_than_one_gpu_and_reads_its_traffic_figure():
     """Host logic of bench.py that needs no GPU: the one-GPU rule and the profile line it quotes."""
     import json
