@@ -252,7 +252,8 @@ def _bwd(name, q, k, v, o, dout, lse, dq, dk, dv, params):
 
 
 def distr_attn_bwd_ex(q, k, v, o, dout, lse, dq, dk, dv, params):
-    """Backward of distr_attn_fwd_ex (float path): fills dq, dk, dv. lse is the forward's lse_out."""
+    """Backward of distr_attn_fwd_ex (bf16 tensors: matrix-core kernels; float tensors: float
+    arithmetic): fills dq, dk, dv. o and lse are the forward's output and lse_out."""
     return _bwd("distr_attn_bwd_ex", q, k, v, o, dout, lse, dq, dk, dv, params)
 
 
