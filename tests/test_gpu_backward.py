@@ -124,6 +124,9 @@ def test_backward_on_bf16_tensors(base, kw):
             unit = max(1.0, np.abs(r).max())
             print(f"  distr={distr} {what}: max-abs {err.max():.3g} mean-abs {err.mean():.3g} (largest gradient {np.abs(r).max():.3g})", flush=True)
             assert err.max() <= 2e-2 * unit and err.mean() <= 2e-3 * unit, f"{base} distr={distr} {what}"
+            # regression bound: twice the largest errors these kernels showed on any case when
+            # they were tuned (0.65 % / 0.03 % of the gradient's scale)
+            assert err.max() <= 1.3e-2 * unit and err.mean() <= 6e-4 * unit, f"{base} distr={distr} {what}: regression"
         if distr and cfg.n_groups < cfg.d:
             _, perm, _ = oracle.lsh_group(q, p)
             G = cfg.d // cfg.n_groups
