@@ -1,6 +1,6 @@
 // Backward of the attention forward (exact and DistrAttention) for bf16 tensors on the gfx950
-// matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate). Three kernels, no atomics (results do
-// not depend on the run).
+// matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate). Three kernels (and a reduction when the
+// dK/dV launch is split over query heads), no atomics (results do not depend on the run).
 //
 // The paper trains through the approximation (Sec. 4.3, 4.4) and gives no gradient; computed here
 // is the derivative of the forward with every Q block's grouping held fixed. With Q_r the sampled
@@ -19,6 +19,7 @@
 //   bwd_dkv_kernel      one workgroup per 128 keys of a kv head, lane = key; Q~ and dO tiles of 64
 //                       rows of every query head of the group stream through LDS:
 //                       S = Q~ K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q~^T dS
+//   bwd_reduce_kernel   sums the float partial dK, dV of a head-split dK/dV launch
 // In both, the accumulator layout of the first products (registers = streamed rows, lanes =
 // resident rows) is the B-operand layout of the last ones, so P and dS never leave registers; the
 // streamed tiles are read once row-wise (16-byte reads) and once with transposing reads. Tiles are
@@ -298,8 +299,7 @@ __global__ __launch_bounds__(kBwdThreads, 2) void bwd_dq_kernel(
 
   // One tile; the loop is unrolled by two so that every buffer is a fixed object in each copy
   // (the compiler then knows that the loads in flight do not touch the tile being read). Tiles
-  // that need the mask take a copy of their own: a branch inside the body would end the region
-  // in which the vector work is scheduled between the MFMAs.
+  // that need the mask take a copy of the body of their own.
   auto tile_step = [&](auto par_c, auto masked, int n0) __attribute__((always_inline)) {
     constexpr int par = decltype(par_c)::value;
     const char* k_lds = par ? k_lds1 : k_lds0;
