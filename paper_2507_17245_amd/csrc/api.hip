@@ -304,6 +304,8 @@ int attention_bwd(const void* q, const void* k, const void* v, const void* o, co
   int rc = resolve(p, distr, &r);
   if (rc) return rc;
   if (r.pb.side == 1) return fail(DA_ERR_UNSUPPORTED, "the backward pass is built for side = 0 only");
+  if (r.dtype == DA_BF16 && ((size_t)r.pb.N * r.pb.d * 2 >= 0x7fffffffULL || (size_t)r.pb.Nk * r.pb.d * 2 >= 0x7fffffffULL))
+    return fail(DA_ERR_UNSUPPORTED, "a head of 2 GiB or more: the backward kernels address tiles by 32-bit byte offsets");
   const void* in[] = {q, k, v, o, dout, lse};
   void* out[] = {dq, dk, dv};
   for (const void* x : in)

@@ -111,6 +111,19 @@ def test_workspace_bytes():
     assert da.distr_attn_workspace_bytes(_params(n_groups=7)) == 0
 
 
+def test_backward_argument_checks_happen_on_the_host():
+    L = da.lib()
+    L.distr_attn_bwd_ex.argtypes = [ctypes.c_void_p] * 9 + [ctypes.POINTER(da.DaParams)]
+    ptrs = [ctypes.c_void_p(0x10000 * (i + 1)) for i in range(9)]
+    call = lambda p, a=ptrs: L.distr_attn_bwd_ex(*a, ctypes.byref(p))
+    assert call(_params(side=1)) == da.DA_ERR_UNSUPPORTED                       # no backward of the mirrored form
+    assert call(_params(N=1 << 24, d=128, n_groups=64)) == da.DA_ERR_UNSUPPORTED   # a head of 4 GiB
+    assert call(_params(n_groups=24)) == da.DA_ERR_INVALID_ARG
+    assert call(_params(), ptrs[:6] + [ptrs[0]] + ptrs[7:]) == da.DA_ERR_INVALID_ARG   # dq aliases q
+    assert call(_params(), ptrs[:6] + [ptrs[6], ptrs[6], ptrs[8]]) == da.DA_ERR_INVALID_ARG   # dk is dq
+    assert call(_params(), [None] + ptrs[1:]) == da.DA_ERR_INVALID_ARG
+
+
 def test_backward_workspace_bytes():
     """Table + 8 bytes per query row + a copy of q; grouped-query shapes whose dK/dV launch is
     split over the query heads add float partial sums of dk and dv per query head of a kv head;
