@@ -269,8 +269,9 @@ def main():
 
     def backward_table(cfg, tensors, steps):
         """The backward pass for bf16 tensors on the matrix cores (gradient with the grouping held
-        fixed), DistrAttention and exact: three launches (prepare, dQ, dK/dV); the two main kernels
-        execute seven products of d multiply-adds per visible (query, key) pair."""
+        fixed), DistrAttention and exact: three launches (prepare, dQ, dK/dV; a reduction when the
+        dK/dV launch is split over query heads); the two main kernels execute seven products of d
+        multiply-adds per visible (query, key) pair."""
         q, k, v = tensors
         dout = to_dev(W.make_grad(cfg), cfg.dtype)
         o = torch.empty_like(q)
@@ -281,11 +282,17 @@ def main():
         out = {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} Hkv={cfg.Hkv} N={cfg.N} d={cfg.d} bf16 "
                            f"{'causal' if cfg.causal else 'non-causal'} Br={cfg.Br} n_groups={cfg.n_groups}",
                "executed_flops": flops}
-        for name, fwd, bwd, p in (
-                ("distr", da.distr_attn_fwd_ex, da.distr_attn_bwd_ex, da.make_params(q, k, v, n_groups=cfg.n_groups, **common)),
-                ("exact", da.distr_attn_exact_fwd_ex, da.distr_attn_exact_bwd_ex, da.make_params(q, k, v, **common))):
+        # as a training step would: the forward leaves its grouping table (written by the attention
+        # kernel's own LSH stage) and the backward takes it back instead of hashing q again
+        table = torch.empty((cfg.B, cfg.H, cfg.Tq, cfg.d), dtype=torch.uint8, device=dev)
+        for name, fwd, bwd, p, pb in (
+                ("distr", da.distr_attn_fwd_ex, da.distr_attn_bwd_ex,
+                 da.make_params(q, k, v, n_groups=cfg.n_groups, perm_out=table, **common),
+                 da.make_params(q, k, v, n_groups=cfg.n_groups, perm_in=table, **common)),
+                ("exact", da.distr_attn_exact_fwd_ex, da.distr_attn_exact_bwd_ex, da.make_params(q, k, v, **common), None)):
+            pb = pb or p
             fwd(q, k, v, o, p)
-            run = lambda: bwd(q, k, v, o, dout, lse, dq, dk, dv, p)
+            run = lambda: bwd(q, k, v, o, dout, lse, dq, dk, dv, pb)
             run()
             ms_f = ev_time(lambda: fwd(q, k, v, o, p), steps)
             ms = ev_time(run, steps)

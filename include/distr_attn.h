@@ -113,9 +113,10 @@ int distr_attn_exact_fwd(const void *q, const void *k, const void *v, void *o, i
                          int Hkv, int N, int d, int Br, int Bc, int causal);
 
 /* The same two operations with every option of da_params. In the bf16 forward with at most 16
- * projections and neither perm_in nor perm_out / hash_out, the attention kernel runs the LSH stage
- * of each query block in that block's own workgroup (same arithmetic and tables as
- * distr_attn_lsh_group, no table is written); otherwise the stage is a kernel of its own. */
+ * projections and neither perm_in nor hash_out, the attention kernel runs the LSH stage of each
+ * query block in that block's own workgroup (same arithmetic and tables as distr_attn_lsh_group;
+ * the table is written only if perm_out is given, e.g. to hand it to the backward pass as
+ * perm_in); otherwise the stage is a kernel of its own. */
 int distr_attn_fwd_ex(const void *q, const void *k, const void *v, void *o, const da_params *p);
 int distr_attn_exact_fwd_ex(const void *q, const void *k, const void *v, void *o, const da_params *p);
 

@@ -263,9 +263,11 @@ int attention(const void* q, const void* k, const void* v, void* o, const da_par
     distr = false;
   }
   if (distr) {
-    // bf16 path, up to 16 projections, no table asked for: the attention kernel hashes and groups
-    // its own Q block in its prologue (same arithmetic as the LSH kernel) and no table is written.
-    const bool lsh_in_kernel = r.dtype == DA_BF16 && r.pb.side == 0 && !p->perm_in && !p->perm_out && !p->hash_out && r.pb.n_planes <= 16;
+    // bf16 path, up to 16 projections, no hashes asked for: the attention kernel hashes and groups
+    // its own Q block in its prologue (same arithmetic as the LSH kernel); the table is written
+    // only if the caller gave perm_out.
+    const bool lsh_in_kernel = r.dtype == DA_BF16 && r.pb.side == 0 && !p->perm_in && !p->hash_out && r.pb.n_planes <= 16;
+    if (lsh_in_kernel) r.pb.perm_w = p->perm_out;
     const bool run_lsh = !p->perm_in && !lsh_in_kernel;
     uint8_t* table = nullptr;
     rc = get_scratch(p, r, run_lsh && !p->perm_out, no_alloc, &table, &kt);

@@ -162,7 +162,8 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     bf16* __restrict__ o, const uint8_t* __restrict__ perm, const f16* __restrict__ kt, int Npad,
     int H, int Hkv, int N, int Nk, int Tq, int causal, float scale_log2e, int total_units, int n_planes,
-    int gray_mode, uint64_t lsh_seed, float* __restrict__ lse, const char* __restrict__ rtab) {
+    int gray_mode, uint64_t lsh_seed, float* __restrict__ lse, const char* __restrict__ rtab,
+    uint8_t* __restrict__ perm_w) {
   using C = Cfg<D, BR, BC, KRED, DISTR, NG>;
   constexpr float kSumTrigger = (BC / 2) * 256.0f;   // BC/2 keys per lane and tile, each at most 2^kTau
   using kx8 = typename std::conditional<DISTR, f16x8, bf16x8>::type;
@@ -457,6 +458,10 @@ __global__ __launch_bounds__(BR * 2, (Cfg<D, BR, BC, KRED, DISTR, NG>::WAVES_PER
     }
     if constexpr (QSTAGE) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    // the table of the workgroup's own LSH stage, for a caller that wants it (e.g. to hand it to
+    // the backward pass)
+    if (perm == nullptr && perm_w != nullptr)
+      for (int i = tid; i < D; i += C::T) perm_w[((size_t)bh * Tq + t) * D + i] = perm_lds[i];
     if constexpr (NG < KRED) {
       // Rows NG..KRED-1 of K_f^T pad the contraction: zeroed once (after the LSH stage, which may
       // have borrowed them), the fusion never writes them; visible to every wave after the
@@ -889,7 +894,8 @@ hipError_t launch_one(const void* q, const void* k, const void* v, void* o, cons
                      stream, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, perm, (const f16*)kt,
                      (pb.Nk + kKtPad - 1) / kKtPad * kKtPad, pb.H, pb.Hkv, pb.N, pb.Nk, Tq, causal_mode,
                      scale_log2e, (int)units, pb.n_planes, pb.gray_mode, pb.seed, pb.lse,
-                     (DISTR && kt) ? (const char*)kt + kt_copy_bytes(pb.B, pb.Hkv, pb.d, pb.Nk) : nullptr);
+                     (DISTR && kt) ? (const char*)kt + kt_copy_bytes(pb.B, pb.Hkv, pb.d, pb.Nk) : nullptr,
+                     DISTR ? pb.perm_w : nullptr);
   return hipGetLastError();
 }
 

@@ -70,6 +70,8 @@ struct Problem {
               // per K block of Bc rows (float-arithmetic kernel)
   int Bc;     // rows of a K block (only side 1 depends on it)
   float* lse; // optional device [B][H][N]: log-sum-exp of every row's visible scores (natural log)
+  uint8_t* perm_w = nullptr;   // optional device [B][H][Tq][d]: where the bf16 attention kernel's own LSH
+                               // stage leaves its table
 };
 
 // Launchers (defined next to their kernels). All return hipError_t of the launch.

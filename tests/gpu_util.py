@@ -15,11 +15,12 @@ def to_dev(x, dtype):
 
 
 def run_gpu(cfg, q, k, v, distr=True, want_tables=False, n_groups=None, lsh_seed=None, gray_mode=0,
-            scale=0.0, perm_in=None, lse_out=None):
+            scale=0.0, perm_in=None, lse_out=None, want_perm_only=False):
     """One forward through the C ABI. -> (o float64 numpy, perm uint8 or None, hash uint32 or None).
     scale 0 = the library's default 1/sqrt(d); perm_in: a grouping table (numpy uint8) to use
     instead of the LSH stage; lse_out: a float32 device tensor [B, H, N] the call fills with the
-    rows' log-sum-exp."""
+    rows' log-sum-exp; want_perm_only: ask for the permutation table alone (no hashes), which the
+    bf16 attention kernel's own LSH stage then writes (returned in place of perm)."""
     tq, tk, tv = (to_dev(x, cfg.dtype) for x in (q, k, v))
     o = torch.full_like(tq, float("nan"))
     perm = hsh = None
@@ -27,6 +28,8 @@ def run_gpu(cfg, q, k, v, distr=True, want_tables=False, n_groups=None, lsh_seed
         shape = (cfg.B, cfg.Hkv, cfg.Tk, cfg.d) if cfg.side == 1 else (cfg.B, cfg.H, cfg.Tq, cfg.d)
         perm = torch.zeros(shape, dtype=torch.uint8, device="cuda")
         hsh = torch.zeros(shape, dtype=torch.int32, device="cuda")
+    if want_perm_only:
+        perm = torch.full((cfg.B, cfg.H, cfg.Tq, cfg.d), 255, dtype=torch.uint8, device="cuda")
     t_perm_in = None if perm_in is None else torch.from_numpy(np.ascontiguousarray(perm_in, dtype=np.uint8)).cuda()
     p = da.make_params(tq, tk, tv, Br=cfg.Br, Bc=cfg.Bc,
                        n_groups=cfg.n_groups if n_groups is None else n_groups, causal=cfg.causal,
@@ -41,6 +44,8 @@ def run_gpu(cfg, q, k, v, distr=True, want_tables=False, n_groups=None, lsh_seed
     o_np = o.float().cpu().numpy().astype(np.float64)
     if want_tables:
         return o_np, perm.cpu().numpy(), hsh.cpu().numpy().view(np.uint32)
+    if want_perm_only:
+        return o_np, perm.cpu().numpy(), None
     return o_np, None, None
 
 

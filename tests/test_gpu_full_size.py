@@ -67,6 +67,10 @@ def test_full_size_parity(name, n_groups):
     # its own Q block, and must give the same output bit for bit
     o_self, _, _ = U.run_gpu(cfg, q, k, v, distr=True, want_tables=False)
     assert np.array_equal(o_self, o_gpu), "in-kernel LSH and LSH kernel disagree"
+    if cfg.dtype == "bf16" and n_groups < cfg.d:
+        # and its table, written on request, is the oracle's on every block
+        _, perm_own, _ = U.run_gpu(cfg, q, k, v, distr=True, want_perm_only=True)
+        assert np.array_equal(perm_own, perm_ref), "table of the attention kernel's own LSH stage differs"
     del o_gpu, o_self
     o_ex, _, _ = U.run_gpu(cfg, q, k, v, distr=False)
     ref_ex = oracle.exact_fwd_tiles(q, k, v, p, tiles)

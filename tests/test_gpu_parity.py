@@ -64,6 +64,11 @@ def test_small_cases_match_oracle(cfg):
     # same tables, so the same output bit for bit
     o_self, _, _ = U.run_gpu(cfg, q, k, v, distr=True, want_tables=False)
     assert np.array_equal(o_self, o_gpu), "in-kernel LSH and LSH kernel disagree"
+    if cfg.dtype == "bf16" and cfg.n_groups < cfg.d:
+        # asked for the table alone, that stage writes it: the oracle's, bit for bit
+        o_own, perm_own, _ = U.run_gpu(cfg, q, k, v, distr=True, want_perm_only=True)
+        assert np.array_equal(perm_own, perm_ref), "table of the attention kernel's own LSH stage differs"
+        assert np.array_equal(o_own, o_gpu)
     o_ex, _, _ = U.run_gpu(cfg, q, k, v, distr=False)
     U.assert_close(o_ex, oracle.exact_fwd(q, k, v, p), cfg.dtype, "exact")
 
@@ -173,7 +178,8 @@ def test_projections_that_nearly_cancel(base, kw):
     assert near_zero > proj[..., 0].size // 2
     o_gpu, perm_gpu, hash_gpu = U.run_gpu(cfg, q, k, v, distr=True, want_tables=True)
     assert np.array_equal(hash_gpu, hash_ref) and np.array_equal(perm_gpu, perm_ref)
-    o_self, _, _ = U.run_gpu(cfg, q, k, v, distr=True, want_tables=False)    # the attention kernel's own LSH stage
+    o_self, perm_self, _ = U.run_gpu(cfg, q, k, v, distr=True, want_perm_only=True)    # the attention kernel's own LSH stage
+    assert np.array_equal(perm_self, perm_ref), "table of the attention kernel's own LSH stage differs"
     assert np.array_equal(o_self, o_gpu), "in-kernel LSH and LSH kernel disagree"
     U.assert_close(o_gpu, oracle.distr_fwd(q, k, v, p), cfg.dtype, "near-cancelling projections")
 
